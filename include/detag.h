@@ -1,0 +1,240 @@
+/*
+ * detag.h — C ABI of the DeTAG hot path on one AMD MI355X (gfx950).
+ *
+ * The library simulates all n workers of a decentralized data-parallel run on
+ * one GPU.  Every state matrix (models X, gradient trackers Y, gradients G) is
+ * n x ld row-major in device memory: row i is worker i, the d parameters of a
+ * worker are contiguous, ld >= d is the row pitch in elements, and the columns
+ * [d, ld) are padding the library neither reads nor writes.
+ *
+ * Paper: Lu & De Sa, "Optimal Complexity in Decentralized Training"
+ * (arXiv 2006.08085).  Each entry point cites the passage that defines it.
+ *
+ * Conventions shared by all entry points
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; the
+ *     library never frees or keeps them after the call's work is enqueued.
+ *     All other pointers are HOST pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued on it; no entry point synchronises the
+ *     host unless its comment says so.  Results written to *_dev outputs are
+ *     valid once the stream reaches them.
+ *   - Calls return a detag_status; nothing throws or aborts across the ABI.
+ *     detag_last_error() gives the text of the last failure.
+ *   - One context serves one stream at a time; calls on one context are not
+ *     re-entrant.  State matrices passed to one call must not overlap unless
+ *     the comment allows it.
+ */
+#ifndef DETAG_H
+#define DETAG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct detag_ctx detag_ctx; /* opaque; owned by the library */
+
+typedef enum {
+  DETAG_OK = 0,
+  DETAG_EINVAL = 1,                /* bad argument (null, size, range, alignment) */
+  DETAG_ENOT_DOUBLY_STOCHASTIC = 2,/* a row or column of W does not sum to 1, or a weight is negative */
+  DETAG_EDISCONNECTED = 3,         /* the support graph of W is not connected (lambda = 1) */
+  DETAG_EUNSUPPORTED = 4,          /* valid request this build has no kernel for */
+  DETAG_ENOMEM = 5,                /* host or device allocation failed */
+  DETAG_EHIP = 6                   /* HIP runtime error, or no GPU present */
+} detag_status;
+
+/* Storage type of X and Y.  Gradients are always fp32; arithmetic is fp32. */
+typedef enum { DETAG_F32 = 0, DETAG_BF16 = 1 } detag_dtype;
+
+typedef enum {
+  DETAG_TOPO_RING = 0,           /* cycle over n workers (n = 2: one edge; n = 1: no edge) */
+  DETAG_TOPO_TORUS2D = 1,        /* rows x cols grid with wrap-around, n = rows*cols */
+  DETAG_TOPO_RANDOM_REGULAR = 2, /* seeded random `degree`-regular graph (degree even) */
+  DETAG_TOPO_EDGES = 3,          /* caller's undirected edge list */
+  DETAG_TOPO_CSR = 4             /* caller's complete W in CSR, see below */
+} detag_topo_kind;
+
+typedef enum {
+  DETAG_W_UNIFORM = 0,   /* 1/(deg+1) on every edge and self-loop; regular graphs only */
+  DETAG_W_METROPOLIS = 1 /* 1/(1+max(deg_i,deg_j)) per edge, remainder on the diagonal */
+} detag_weight_kind;
+
+/*
+ * The gossip matrix W of the paper's class W_n ("Protocol Layer": doubly
+ * stochastic, W_ij != 0 only on edges of the graph or the diagonal).
+ *   kind RING / TORUS2D / RANDOM_REGULAR / EDGES: the library builds W from
+ *     the graph with `weights`.
+ *   kind CSR: the caller gives W itself.  Row i of the CSR lists the pairs
+ *     (j, W_ji) — the terms of the gossip sum of worker i, which reads
+ *     column i of W; the self term must be listed.  `weights` is ignored.
+ *   kappa: slack matrix W_kappa = kappa*W + (1-kappa)*I ("Experiments",
+ *     second experiment); 1.0 leaves W unchanged.  Must be in (0, 1].
+ * All arrays are host memory, read during detag_create only.
+ */
+typedef struct {
+  int32_t kind;          /* detag_topo_kind */
+  int32_t weights;       /* detag_weight_kind */
+  int32_t rows, cols;    /* TORUS2D only */
+  int32_t degree;        /* RANDOM_REGULAR only */
+  uint64_t seed;         /* RANDOM_REGULAR only */
+  double kappa;
+  int64_t n_edges;       /* EDGES: number of pairs in `edges` */
+  const int32_t *edges;  /* EDGES: 2*n_edges vertex ids, pairs (a,b), a != b, no repeats */
+  const int32_t *rowptr; /* CSR: n+1 offsets */
+  const int32_t *colidx; /* CSR: nnz worker ids j */
+  const double *vals;    /* CSR: nnz weights W_ji */
+} detag_topology;
+
+/* Which form of the phase update detag_step applies. */
+typedef enum {
+  DETAG_VARIANT_ATC = 0, /* matrix form in the proof of Theorem 3: Y+ = M(Y+Gnew-Gold), X+ = M(X-alpha*Y) */
+  DETAG_VARIANT_ALG2 = 1 /* Algorithm 2 as printed: gossip first, then x = x~ - alpha*y, y = y + g(k) - g(k-1) */
+} detag_variant;
+
+/* Which kernels run the accelerated gossip; AUTO picks the fastest that applies. */
+typedef enum {
+  DETAG_PATH_AUTO = 0,
+  DETAG_PATH_PER_ROUND = 1, /* one launch per gossip round, state streamed through HBM every round */
+  DETAG_PATH_FUSED = 2      /* all K rounds on chip, one pass over the state; EUNSUPPORTED if n does not fit */
+} detag_path;
+
+/*
+ * Build W, check it, compute its spectrum and eta, and upload the neighbour
+ * lists.  Host work only, plus one small synchronous upload.
+ *   n  workers (>= 1), d parameters per worker (>= 1), ld row pitch (>= d).
+ *   state: storage type of X and Y for every later call on this context.
+ * Rejects: n < 1, d < 1, ld < d, kappa outside (0,1], a malformed graph or
+ * CSR (EINVAL); row/column sums off 1 by more than 1e-9 or negative weights
+ * (ENOT_DOUBLY_STOCHASTIC); a disconnected support graph (EDISCONNECTED).
+ * lambda = max(|lambda_2|, |lambda_n|) ("Protocol Layer") and
+ * eta = (1-sqrt(1-lambda^2))/(1+sqrt(1-lambda^2)) (Algorithm 3) are computed
+ * when W is symmetric; for an asymmetric W they are NaN and every call must
+ * pass eta explicitly.  n = 1: W = [1], lambda = eta = 0.
+ * Without a GPU the context is still created (spectrum and CSR can be
+ * queried); every device entry point then returns DETAG_EHIP.
+ * On failure *out is NULL and detag_last_error(NULL) has the reason.
+ */
+detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int64_t ld,
+                          detag_dtype state, detag_ctx **out);
+
+/* Frees the context and its device scratch.  Synchronises the device. NULL is ignored. */
+void detag_destroy(detag_ctx *ctx);
+
+/* lambda_2, lambda_n, lambda, eta of the context's W (host doubles; any may be NULL). */
+detag_status detag_get_spectrum(const detag_ctx *ctx, double *lambda2, double *lambdan,
+                                double *lambda, double *eta);
+
+/* Host views of W as stored (row i = pairs (j, W_ji), self included, j ascending).
+ * The arrays belong to the context and live until detag_destroy. */
+detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const int32_t **rowptr,
+                           const int32_t **colidx, const double **vals);
+
+/* Select the gossip kernels (default AUTO).  FUSED is refused with EUNSUPPORTED
+ * if the context's n has no on-chip kernel. */
+detag_status detag_set_path(detag_ctx *ctx, detag_path path);
+
+/* 1 if the fused (all K rounds on chip) kernels exist for this context, else 0. */
+int32_t detag_has_fused(const detag_ctx *ctx);
+
+/*
+ * Accelerated gossip, Algorithm 3, for all workers at once, in place:
+ *   z_{-1} = z_0;  z_{r+1} = (1+eta) * sum_{j in N_i + i} z_{r,j} W_ji - eta * z_{r-1,i},  r = 0..K-1.
+ * Z_dev: n x ld matrix of the context's state type; holds z_K on return.
+ * K >= 0 (K = 0 is a no-op).  eta in [0,1), or negative to use the context's eta.
+ * The per-round path allocates its scratch (two n x ld matrices) on first use.
+ */
+detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double eta, void *stream);
+
+/*
+ * Tracker update of Algorithm 2: Y <- Y + Gnew - Gold, in place on Y.
+ * Y_dev: state type; Gnew_dev, Gold_dev: fp32, n x ld.
+ */
+detag_status detag_track(detag_ctx *ctx, void *Y_dev, const float *Gnew_dev, const float *Gold_dev,
+                         void *stream);
+
+/*
+ * One DeTAG phase of length K (Algorithm 2 with R = K, all workers), in place
+ * on X and Y.  Gradients are inputs: Gnew = this phase's gradient buffer g(k),
+ * Gold = the previous one g(k-1); the caller swaps them afterwards.
+ *   ATC : X+ = M(X - alpha*Y);  Y+ = M(Y + Gnew - Gold)       (proof of Theorem 3)
+ *   ALG2: X+ = M(X) - alpha*M(Y);  Y+ = M(Y) + Gnew - Gold    (Algorithm 2 as printed)
+ * with M the K-step accelerated gossip above.  eta as in detag_gossip_accel.
+ * X_dev, Y_dev: state type; Gnew_dev, Gold_dev: fp32.  The four must not overlap.
+ */
+detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *Gnew_dev,
+                        const float *Gold_dev, double alpha, int32_t K, double eta,
+                        detag_variant variant, void *stream);
+
+/*
+ * D-PSGD, the baseline of the "Experiments" section: X <- W^T X - alpha*G,
+ * in place on X (one plain gossip step of the models, then the local step).
+ */
+detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, double alpha, void *stream);
+
+/* Output of Algorithm 2: xbar[c] = (1/n) sum_i X[i,c].  xbar_dev: d floats. */
+detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream);
+
+/*
+ * Consensus distance ||X - 1 xbar^T||_F^2 that the proof of Theorem 3 bounds.
+ * sumsq_dev: one double in device memory.  Deterministic (fixed reduction order).
+ */
+detag_status detag_consensus_error(detag_ctx *ctx, const void *X_dev, double *sumsq_dev, void *stream);
+
+/*
+ * Stochastic gradient of f_i(x) = 1/2 sum_c h_c (x_c - b_ic)^2 at every
+ * worker's own model (the gradient query of Algorithm 2):
+ *   G[i,c] = h[c]*(X[i,c] - b[i,c]) + sigma * z[i,c]
+ * X_dev: state type; h_dev: fp32, length ld (shared) or n x ld (h_per_worker != 0);
+ * b_dev: fp32 n x ld; G_dev: fp32 n x ld (must not overlap X).
+ * Noise z: if noise_dev != NULL it is an fp32 n x ld array of standard normals;
+ * else if sigma != 0 it is generated in the kernel from the counter
+ * (seed, step, worker, column) with Philox-4x32-10 + Box-Muller:
+ *   block q = c/4, counter = (q mod 2^32, q div 2^32, i, step), key = (seed mod 2^32, seed div 2^32),
+ *   u(r) = ((r>>9)+0.5)*2^-23,  z[4q+0], z[4q+1] = sqrt(-2 ln u(r0)) * (cos, sin)(2 pi u(r1)),
+ *   z[4q+2], z[4q+3] likewise from (r2, r3).
+ */
+detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const float *h_dev,
+                                       int32_t h_per_worker, const float *b_dev,
+                                       const float *noise_dev, float sigma, uint64_t seed,
+                                       uint32_t step, float *G_dev, void *stream);
+
+/*
+ * Gradient of f_i(x) = 1/2 ||A_i x - b_i||^2:  G[i,:] = A_i^T (A_i X[i,:] - b_i).
+ * A_dev: fp32 n x m x d (row pitch d), b_dev: fp32 n x m, G_dev: fp32 n x ld.
+ * Uses a context-owned scratch of n*m floats (allocated on first use).
+ */
+detag_status detag_grad_lstsq(detag_ctx *ctx, const void *X_dev, const float *A_dev,
+                              const float *b_dev, int32_t m, float *G_dev, void *stream);
+
+/*
+ * Mini-batch gradient of multinomial logistic regression (mean cross-entropy),
+ * every worker on its own batch, with bf16 MFMA contractions and fp32
+ * accumulation.  A row of X holds C*F weights (class-major) then C biases, so
+ * the context's d must equal C*F + C.
+ *   feat_dev  : bf16 (uint16 bit patterns), n x S x F — worker i's local samples
+ *   labels_dev: int32 n x S, values in [0, C)
+ *   batch_dev : int32 n x B, sample indices in [0, S) for this step
+ *   G_dev     : fp32 n x ld;  loss_dev: fp32 n (mean loss of each batch), may be NULL
+ * Limits: C <= 10, F % 32 == 0, B % 32 == 0, B <= 256.  X must be fp32.
+ * The fp32 weights and the fp32 softmax residuals are split into three bf16
+ * terms each before the MFMA, so the result carries fp32 accuracy with respect
+ * to the bf16 features.
+ */
+detag_status detag_grad_softmax_bf16(detag_ctx *ctx, const void *X_dev, const uint16_t *feat_dev,
+                                     const int32_t *labels_dev, const int32_t *batch_dev,
+                                     int32_t S, int32_t F, int32_t C, int32_t B, float *G_dev,
+                                     float *loss_dev, void *stream);
+
+/* Text of the last failure on this context (or of the last failed detag_create
+ * on this thread when ctx is NULL).  Never NULL. */
+const char *detag_last_error(const detag_ctx *ctx);
+
+/* Library version string. */
+const char *detag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DETAG_H */

@@ -11,7 +11,7 @@ numpy integers; it is pinned to the authors' known-answer vectors.
 Counter layout for the noise of (step t, worker i, columns 4q..4q+3):
     counter = (q mod 2^32, q div 2^32, i, t),  key = (seed mod 2^32, seed div 2^32)
 The four output words r0..r3 give four normals:
-    u(r)  = ((r >> 8) + 1/2) * 2^-24           (24 bits, never 0 or 1)
+    u(r)  = ((r >> 9) + 1/2) * 2^-23           (23 bits + 1/2: exact in fp32, never 0 or 1)
     z0,z1 = sqrt(-2 ln u(r0)) * (cos, sin)(2 pi u(r1))
     z2,z3 = sqrt(-2 ln u(r2)) * (cos, sin)(2 pi u(r3))
 """
@@ -46,7 +46,7 @@ def philox4x32_10(ctr, key):
 
 
 def _unit(r: np.ndarray) -> np.ndarray:
-    return ((r >> np.uint32(8)).astype(np.float64) + 0.5) * (2.0 ** -24)
+    return ((r >> np.uint32(9)).astype(np.float64) + 0.5) * (2.0 ** -23)
 
 
 def normal_noise(seed: int, step: int, n: int, cols) -> np.ndarray:

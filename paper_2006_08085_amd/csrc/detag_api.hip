@@ -1,0 +1,419 @@
+// C ABI of the DeTAG hot path (see include/detag.h): argument checks, the
+// context, and the order in which kernels are enqueued.  No arithmetic of the
+// method happens on the host after detag_create.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "detag_internal.h"
+
+using namespace detag;
+
+struct detag_ctx {
+  HostW W;
+  Shape shape{};
+  bool has_device = false;
+  int device = -1;
+  int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
+  float *d_vals = nullptr;
+  void *scratch[2] = {nullptr, nullptr};  // per-round path: n x ld state matrices
+  double *d_partials = nullptr;           // consensus-error partial sums
+  float *d_resid = nullptr;               // least-squares residuals
+  int64_t resid_count = 0;
+  detag_path path = DETAG_PATH_AUTO;
+  mutable std::string err;
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+detag_status set_err(const detag_ctx *ctx, detag_status st, const std::string &msg) {
+  if (ctx) ctx->err = msg; else g_create_err = msg;
+  return st;
+}
+
+detag_status hip_fail(const detag_ctx *ctx, const char *what, int rc) {
+  char buf[256];
+  std::snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(static_cast<hipError_t>(rc)));
+  return set_err(ctx, DETAG_EHIP, buf);
+}
+
+size_t state_bytes(const Shape &s) { return size_t(s.n) * size_t(s.ld) * (s.bf16 ? 2 : 4); }
+
+detag_status need_device(const detag_ctx *ctx) {
+  if (!ctx) return DETAG_EINVAL;
+  if (!ctx->has_device) return set_err(ctx, DETAG_EHIP, "no GPU was present when this context was created");
+  return DETAG_OK;
+}
+
+detag_status need_scratch(detag_ctx *ctx, int count) {
+  for (int k = 0; k < count; ++k)
+    if (!ctx->scratch[k]) {
+      hipError_t e = hipMalloc(&ctx->scratch[k], state_bytes(ctx->shape));
+      if (e != hipSuccess) {
+        ctx->scratch[k] = nullptr;
+        (void)hipGetLastError();
+        return set_err(ctx, DETAG_ENOMEM, "could not allocate the per-round gossip scratch");
+      }
+    }
+  return DETAG_OK;
+}
+
+bool misaligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+
+detag_status resolve_eta(const detag_ctx *ctx, double eta_in, float *eta_out) {
+  double eta = eta_in;
+  if (eta < 0) {
+    eta = ctx->W.eta;
+    if (std::isnan(eta))
+      return set_err(ctx, DETAG_EINVAL, "W is not symmetric, so it has no stored eta: pass eta explicitly");
+  }
+  if (!(eta >= 0.0 && eta < 1.0)) return set_err(ctx, DETAG_EINVAL, "eta must be in [0, 1)");
+  *eta_out = float(eta);
+  return DETAG_OK;
+}
+
+DevCsr dev_csr(const detag_ctx *ctx) {
+  DevCsr w;
+  w.rowptr = ctx->d_rowptr, w.colidx = ctx->d_colidx, w.vals = ctx->d_vals;
+  return w;
+}
+
+enum Chosen { kPerRound, kFusedStructured, kFusedGeneric };
+
+detag_status choose_path(const detag_ctx *ctx, Chosen *out) {
+  const bool fs = fused_structured_available(ctx->W), fg = fused_generic_available(ctx->W, ctx->shape);
+  if (ctx->path == DETAG_PATH_PER_ROUND) return *out = kPerRound, DETAG_OK;
+  if (fs) return *out = kFusedStructured, DETAG_OK;
+  if (fg) return *out = kFusedGeneric, DETAG_OK;
+  if (ctx->path == DETAG_PATH_FUSED)
+    return set_err(ctx, DETAG_EUNSUPPORTED, "no fused kernel for this topology and n");
+  return *out = kPerRound, DETAG_OK;
+}
+
+// Algorithm 3 with one launch per round.  z_r lives in the caller's buffer A or
+// in scratch; a round may write over its own z_{r-1} (each output element reads
+// only its own previous value) but never over z_r, which every neighbour reads.
+detag_status gossip_per_round(detag_ctx *ctx, void *A, int K, float eta, void *stream) {
+  if (K == 0) return DETAG_OK;
+  const int nscratch = (K % 2 == 1 && K >= 3) ? 2 : 1;
+  if (detag_status st = need_scratch(ctx, nscratch)) return st;
+  void *B = ctx->scratch[0], *C = ctx->scratch[1];
+  const Shape &s = ctx->shape;
+  const DevCsr w = dev_csr(ctx);
+  const float cm = 1.f + eta, cp = -eta;
+  int rc = launch_gossip_round(s, w, A, A, B, cm, cp, stream);  // z1 -> B
+  if (rc) return hip_fail(ctx, "gossip round", rc);
+  if (K == 1) {
+    rc = launch_copy_state(s, B, A, stream);
+    return rc ? hip_fail(ctx, "copy", rc) : DETAG_OK;
+  }
+  int r = 1;           // next round computes z_{r+1}
+  void *cur = B, *prev = A;
+  if (K % 2 == 1) {    // shift parity once through the third buffer: z2 -> C, z3 -> A
+    rc = launch_gossip_round(s, w, B, A, C, cm, cp, stream);
+    if (!rc) rc = launch_gossip_round(s, w, C, B, A, cm, cp, stream);
+    if (rc) return hip_fail(ctx, "gossip round", rc);
+    r = 3, cur = A, prev = C;
+  }
+  for (; r < K; ++r) {  // z_{r+1} overwrites z_{r-1}
+    rc = launch_gossip_round(s, w, cur, prev, prev, cm, cp, stream);
+    if (rc) return hip_fail(ctx, "gossip round", rc);
+    void *t = cur; cur = prev; prev = t;
+  }
+  if (cur != A) return set_err(ctx, DETAG_EHIP, "internal: gossip result not in the caller's buffer");
+  return DETAG_OK;
+}
+
+detag_status check_state_ptr(const detag_ctx *ctx, const void *p, const char *name) {
+  if (!p) return set_err(ctx, DETAG_EINVAL, std::string(name) + " is NULL");
+  if (misaligned(p, ctx->shape.bf16 ? 2 : 4)) return set_err(ctx, DETAG_EINVAL, std::string(name) + " is misaligned");
+  return DETAG_OK;
+}
+
+detag_status check_f32_ptr(const detag_ctx *ctx, const void *p, const char *name) {
+  if (!p) return set_err(ctx, DETAG_EINVAL, std::string(name) + " is NULL");
+  if (misaligned(p, 4)) return set_err(ctx, DETAG_EINVAL, std::string(name) + " is misaligned");
+  return DETAG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int64_t ld, detag_dtype state,
+                          detag_ctx **out) {
+  if (!out) return set_err(nullptr, DETAG_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (n < 1 || n > 65535) return set_err(nullptr, DETAG_EINVAL, "n must be in [1, 65535]");
+  if (d < 1) return set_err(nullptr, DETAG_EINVAL, "d must be >= 1");
+  if (ld < d) return set_err(nullptr, DETAG_EINVAL, "ld must be >= d");
+  if (state != DETAG_F32 && state != DETAG_BF16) return set_err(nullptr, DETAG_EINVAL, "unknown state dtype");
+  detag_ctx *ctx = new (std::nothrow) detag_ctx();
+  if (!ctx) return set_err(nullptr, DETAG_ENOMEM, "out of host memory");
+  std::string err;
+  detag_status st;
+  try {
+    st = build_gossip_matrix(topo, n, ctx->W, err);
+  } catch (const std::bad_alloc &) {
+    st = DETAG_ENOMEM, err = "out of host memory";
+  }
+  if (st != DETAG_OK) {
+    delete ctx;
+    return set_err(nullptr, st, err);
+  }
+  ctx->shape.n = n, ctx->shape.d = d, ctx->shape.ld = ld, ctx->shape.bf16 = state == DETAG_BF16;
+
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || count < 1) {
+    (void)hipGetLastError();
+    ctx->has_device = false;
+    *out = ctx;
+    return DETAG_OK;
+  }
+  ctx->has_device = true;
+  (void)hipGetDevice(&ctx->device);
+  const size_t nnz = ctx->W.colidx.size();
+  std::vector<float> vals32(nnz);
+  for (size_t k = 0; k < nnz; ++k) vals32[k] = float(ctx->W.vals[k]);
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&ctx->d_rowptr), (size_t(n) + 1) * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_colidx), nnz * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_vals), nnz * sizeof(float));
+  if (e == hipSuccess)
+    e = hipMalloc(reinterpret_cast<void **>(&ctx->d_partials), size_t(consensus_partials_count(ctx->shape)) * sizeof(double));
+  if (e == hipSuccess)
+    e = hipMemcpy(ctx->d_rowptr, ctx->W.rowptr.data(), (size_t(n) + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_colidx, ctx->W.colidx.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(ctx->d_vals, vals32.data(), nnz * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    const int rc = int(e);
+    detag_destroy(ctx);
+    return hip_fail(nullptr, "uploading the gossip matrix", rc);
+  }
+  *out = ctx;
+  return DETAG_OK;
+}
+
+void detag_destroy(detag_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->has_device) {
+    (void)hipDeviceSynchronize();
+    (void)hipFree(ctx->d_rowptr);
+    (void)hipFree(ctx->d_colidx);
+    (void)hipFree(ctx->d_vals);
+    (void)hipFree(ctx->d_partials);
+    (void)hipFree(ctx->d_resid);
+    (void)hipFree(ctx->scratch[0]);
+    (void)hipFree(ctx->scratch[1]);
+  }
+  delete ctx;
+}
+
+detag_status detag_get_spectrum(const detag_ctx *ctx, double *lambda2, double *lambdan, double *lambda, double *eta) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (lambda2) *lambda2 = ctx->W.lambda2;
+  if (lambdan) *lambdan = ctx->W.lambdan;
+  if (lambda) *lambda = ctx->W.lambda;
+  if (eta) *eta = ctx->W.eta;
+  return DETAG_OK;
+}
+
+detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const int32_t **rowptr,
+                           const int32_t **colidx, const double **vals) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (n) *n = ctx->W.n;
+  if (nnz) *nnz = int64_t(ctx->W.colidx.size());
+  if (rowptr) *rowptr = ctx->W.rowptr.data();
+  if (colidx) *colidx = ctx->W.colidx.data();
+  if (vals) *vals = ctx->W.vals.data();
+  return DETAG_OK;
+}
+
+detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (path != DETAG_PATH_AUTO && path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_FUSED)
+    return set_err(ctx, DETAG_EINVAL, "unknown path");
+  if (path == DETAG_PATH_FUSED && !detag_has_fused(ctx))
+    return set_err(ctx, DETAG_EUNSUPPORTED, "no fused kernel for this topology and n");
+  ctx->path = path;
+  return DETAG_OK;
+}
+
+int32_t detag_has_fused(const detag_ctx *ctx) {
+  if (!ctx) return 0;
+  return fused_structured_available(ctx->W) || fused_generic_available(ctx->W, ctx->shape) ? 1 : 0;
+}
+
+detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double eta, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, Z_dev, "Z_dev")) return st;
+  if (K < 0) return set_err(ctx, DETAG_EINVAL, "K must be >= 0");
+  float e;
+  if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
+  if (K == 0) return DETAG_OK;
+  Chosen path;
+  if (detag_status st = choose_path(ctx, &path)) return st;
+  int rc = 0;
+  switch (path) {
+    case kFusedStructured:
+      rc = launch_fused_structured(ctx->shape, ctx->W, 0, Z_dev, nullptr, nullptr, nullptr, 0.f, K, e, stream);
+      break;
+    case kFusedGeneric:
+      rc = launch_fused_generic(ctx->shape, ctx->W, dev_csr(ctx), 0, Z_dev, nullptr, nullptr, nullptr, 0.f, K, e, stream);
+      break;
+    case kPerRound:
+      return gossip_per_round(ctx, Z_dev, K, e, stream);
+  }
+  return rc ? hip_fail(ctx, "fused gossip", rc) : DETAG_OK;
+}
+
+detag_status detag_track(detag_ctx *ctx, void *Y_dev, const float *Gnew_dev, const float *Gold_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, Y_dev, "Y_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gnew_dev, "Gnew_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gold_dev, "Gold_dev")) return st;
+  const int rc = launch_track(ctx->shape, Y_dev, Gnew_dev, Gold_dev, stream);
+  return rc ? hip_fail(ctx, "track", rc) : DETAG_OK;
+}
+
+detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *Gnew_dev, const float *Gold_dev,
+                        double alpha, int32_t K, double eta, detag_variant variant, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Y_dev, "Y_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gnew_dev, "Gnew_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gold_dev, "Gold_dev")) return st;
+  if (X_dev == Y_dev || static_cast<const void *>(Gnew_dev) == X_dev || static_cast<const void *>(Gnew_dev) == Y_dev ||
+      static_cast<const void *>(Gold_dev) == X_dev || static_cast<const void *>(Gold_dev) == Y_dev)
+    return set_err(ctx, DETAG_EINVAL, "X, Y and the gradient buffers must not overlap");
+  if (K < 0) return set_err(ctx, DETAG_EINVAL, "K must be >= 0");
+  if (!std::isfinite(alpha)) return set_err(ctx, DETAG_EINVAL, "alpha must be finite");
+  if (variant != DETAG_VARIANT_ATC && variant != DETAG_VARIANT_ALG2)
+    return set_err(ctx, DETAG_EINVAL, "unknown variant");
+  float e;
+  if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
+  const Shape &s = ctx->shape;
+  const float a = float(alpha);
+  if (K == 0) {  // M is the identity: both variants reduce to the two elementwise updates
+    const int rc = launch_update_track(s, X_dev, Y_dev, Gnew_dev, Gold_dev, a, stream);
+    return rc ? hip_fail(ctx, "update", rc) : DETAG_OK;
+  }
+  Chosen path;
+  if (detag_status st = choose_path(ctx, &path)) return st;
+  const int mode = variant == DETAG_VARIANT_ATC ? 1 : 2;
+  if (path == kFusedStructured) {
+    const int rc = launch_fused_structured(s, ctx->W, mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, K, e, stream);
+    return rc ? hip_fail(ctx, "fused phase", rc) : DETAG_OK;
+  }
+  if (path == kFusedGeneric) {
+    const int rc = launch_fused_generic(s, ctx->W, dev_csr(ctx), mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, K, e, stream);
+    return rc ? hip_fail(ctx, "fused phase", rc) : DETAG_OK;
+  }
+  if (variant == DETAG_VARIANT_ATC) {
+    const int rc = launch_update_track(s, X_dev, Y_dev, Gnew_dev, Gold_dev, a, stream);
+    if (rc) return hip_fail(ctx, "update", rc);
+  }
+  if (detag_status st = gossip_per_round(ctx, X_dev, K, e, stream)) return st;
+  if (detag_status st = gossip_per_round(ctx, Y_dev, K, e, stream)) return st;
+  if (variant == DETAG_VARIANT_ALG2) {
+    const int rc = launch_update_track(s, X_dev, Y_dev, Gnew_dev, Gold_dev, a, stream);
+    if (rc) return hip_fail(ctx, "update", rc);
+  }
+  return DETAG_OK;
+}
+
+detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, double alpha, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (detag_status st = need_scratch(ctx, 1)) return st;
+  int rc = launch_copy_state(ctx->shape, X_dev, ctx->scratch[0], stream);
+  if (!rc) rc = launch_dpsgd(ctx->shape, dev_csr(ctx), ctx->scratch[0], X_dev, G_dev, float(alpha), stream);
+  return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
+}
+
+detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, xbar_dev, "xbar_dev")) return st;
+  const int rc = launch_mean(ctx->shape, X_dev, xbar_dev, stream);
+  return rc ? hip_fail(ctx, "mean", rc) : DETAG_OK;
+}
+
+detag_status detag_consensus_error(detag_ctx *ctx, const void *X_dev, double *sumsq_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (!sumsq_dev || misaligned(sumsq_dev, 8)) return set_err(ctx, DETAG_EINVAL, "sumsq_dev is NULL or misaligned");
+  const int rc = launch_consensus_error(ctx->shape, X_dev, ctx->d_partials, sumsq_dev, stream);
+  return rc ? hip_fail(ctx, "consensus error", rc) : DETAG_OK;
+}
+
+detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const float *h_dev, int32_t h_per_worker,
+                                       const float *b_dev, const float *noise_dev, float sigma, uint64_t seed,
+                                       uint32_t step, float *G_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, h_dev, "h_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, b_dev, "b_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (noise_dev && misaligned(noise_dev, 4)) return set_err(ctx, DETAG_EINVAL, "noise_dev is misaligned");
+  if (static_cast<const void *>(G_dev) == X_dev) return set_err(ctx, DETAG_EINVAL, "G must not overlap X");
+  if (!std::isfinite(sigma)) return set_err(ctx, DETAG_EINVAL, "sigma must be finite");
+  const int rc = launch_grad_quadratic(ctx->shape, X_dev, h_dev, h_per_worker, b_dev, noise_dev, sigma, seed, step,
+                                       G_dev, stream);
+  return rc ? hip_fail(ctx, "quadratic gradient", rc) : DETAG_OK;
+}
+
+detag_status detag_grad_lstsq(detag_ctx *ctx, const void *X_dev, const float *A_dev, const float *b_dev, int32_t m,
+                              float *G_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, A_dev, "A_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, b_dev, "b_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (m < 1) return set_err(ctx, DETAG_EINVAL, "m must be >= 1");
+  const int64_t need = int64_t(ctx->shape.n) * m;
+  if (ctx->resid_count < need) {
+    (void)hipFree(ctx->d_resid);
+    ctx->d_resid = nullptr, ctx->resid_count = 0;
+    if (hipMalloc(reinterpret_cast<void **>(&ctx->d_resid), size_t(need) * sizeof(float)) != hipSuccess) {
+      (void)hipGetLastError();
+      return set_err(ctx, DETAG_ENOMEM, "could not allocate the residual scratch");
+    }
+    ctx->resid_count = need;
+  }
+  const int rc = launch_grad_lstsq(ctx->shape, X_dev, A_dev, b_dev, m, ctx->d_resid, G_dev, stream);
+  return rc ? hip_fail(ctx, "least-squares gradient", rc) : DETAG_OK;
+}
+
+detag_status detag_grad_softmax_bf16(detag_ctx *ctx, const void *X_dev, const uint16_t *feat_dev,
+                                     const int32_t *labels_dev, const int32_t *batch_dev, int32_t S, int32_t F,
+                                     int32_t C, int32_t B, float *G_dev, float *loss_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (ctx->shape.bf16) return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient needs fp32 state");
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (!feat_dev || !labels_dev || !batch_dev) return set_err(ctx, DETAG_EINVAL, "a data pointer is NULL");
+  if (misaligned(feat_dev, 16) || misaligned(labels_dev, 4) || misaligned(batch_dev, 4) ||
+      (loss_dev && misaligned(loss_dev, 4)))
+    return set_err(ctx, DETAG_EINVAL, "a data pointer is misaligned (features need 16 bytes)");
+  if (C < 2 || C > 10 || F < 32 || F % 32 || B < 32 || B % 32 || B > 256 || S < 1)
+    return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient limits: 2 <= C <= 10, F % 32 == 0, B % 32 == 0, B <= 256");
+  if (int64_t(C) * F + C != ctx->shape.d)
+    return set_err(ctx, DETAG_EINVAL, "d must equal C*F + C");
+  const int rc = launch_grad_softmax(ctx->shape, X_dev, feat_dev, labels_dev, batch_dev, S, F, C, B, G_dev, loss_dev,
+                                     stream);
+  if (rc == -1) return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient kernel is not built");
+  return rc ? hip_fail(ctx, "softmax gradient", rc) : DETAG_OK;
+}
+
+const char *detag_last_error(const detag_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+const char *detag_version(void) { return "detag-gfx950 0.1"; }
+
+}  // extern "C"

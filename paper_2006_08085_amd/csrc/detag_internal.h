@@ -1,0 +1,89 @@
+// Internal declarations shared by the host code and the kernel launchers.
+// Nothing here is part of the C ABI (see include/detag.h).
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "detag.h"
+
+namespace detag {
+
+// Structured neighbour patterns the register-resident kernels are compiled for.
+enum Structure : int { kGeneric = 0, kRing = 1, kTorus = 2 };
+
+// The gossip matrix on the host.  Row i of the CSR lists (j, W_ji), j ascending,
+// self included: exactly the terms of worker i's gossip sum.
+struct HostW {
+  int n = 0;
+  std::vector<int32_t> rowptr, colidx;
+  std::vector<double> vals;
+  bool symmetric = false;
+  double lambda2 = 0, lambdan = 0, lambda = 0, eta = 0;  // NaN when not symmetric
+  Structure structure = kGeneric;
+  int trows = 0, tcols = 0;       // torus shape
+  double w_self = 0, w_nb = 0;    // structured patterns: one self weight, one neighbour weight
+  int max_row_nnz = 0;
+};
+
+// Builds, validates and analyses W.  On failure returns the status and fills err.
+detag_status build_gossip_matrix(const detag_topology *topo, int n, HostW &W, std::string &err);
+
+// Eigenvalues (ascending) of a dense symmetric matrix, cyclic Jacobi. a is n*n row-major, destroyed.
+void symmetric_eigenvalues(std::vector<double> &a, int n, std::vector<double> &ev);
+
+// ---------------------------------------------------------------------------
+// Kernel launchers.  All pointers are device pointers; stream is a hipStream_t.
+// Each returns a hipError_t value as int (0 = success).
+// ---------------------------------------------------------------------------
+struct DevCsr {
+  const int32_t *rowptr = nullptr;  // n+1
+  const int32_t *colidx = nullptr;  // nnz
+  const float *vals = nullptr;      // nnz, fp32 copies of W_ji
+};
+
+struct Shape {
+  int n;
+  int64_t d, ld;
+  bool bf16;  // storage of X/Y
+};
+
+// One gossip round, out = c_mix * (W^T cur) + c_prev * prev.  out may alias prev; out != cur.
+int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out,
+                        float c_mix, float c_prev, void *stream);
+// Y += Gnew - Gold
+int launch_track(const Shape &s, void *Y, const float *Gn, const float *Go, void *stream);
+// X -= alpha*Y (old Y); Y += Gnew - Gold   (one pass)
+int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const float *Go, float alpha,
+                        void *stream);
+// X = c_mix * (W^T Xin) - alpha*G  (D-PSGD); Xin != X
+int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
+                 void *stream);
+int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream);
+
+// Fused K-round kernels.  mode: 0 = gossip only on X (Y, Gn, Go unused), 1 = ATC phase, 2 = ALG2 phase.
+// Returns -1 if no kernel exists for this (structure, n).
+bool fused_structured_available(const HostW &W);
+int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, void *Y, const float *Gn,
+                            const float *Go, float alpha, int K, float eta, void *stream);
+bool fused_generic_available(const HostW &W, const Shape &s);
+int launch_fused_generic(const Shape &s, const HostW &W, const DevCsr &w, int mode, void *X, void *Y,
+                         const float *Gn, const float *Go, float alpha, int K, float eta, void *stream);
+
+// Diagnostics
+int launch_mean(const Shape &s, const void *X, float *xbar, void *stream);
+int64_t consensus_partials_count(const Shape &s);
+int launch_consensus_error(const Shape &s, const void *X, double *partials, double *out, void *stream);
+
+// Gradients
+int launch_grad_quadratic(const Shape &s, const void *X, const float *h, int h_per_worker, const float *b,
+                          const float *noise, float sigma, uint64_t seed, uint32_t step, float *G,
+                          void *stream);
+int launch_grad_lstsq(const Shape &s, const void *X, const float *A, const float *b, int m, float *resid,
+                      float *G, void *stream);
+int launch_grad_softmax(const Shape &s, const void *X, const uint16_t *feat, const int32_t *labels,
+                        const int32_t *batch, int S, int F, int C, int B, float *G, float *loss,
+                        void *stream);
+
+}  // namespace detag

@@ -1,0 +1,93 @@
+// Diagnostics: the worker mean (the output line of Algorithm 2) and the
+// consensus distance ||X - 1 xbar^T||_F^2 bounded in the proof of Theorem 3.
+// One lane owns one column and walks the n rows; sums are kept in fp64 so the
+// distance stays meaningful when the workers almost agree.  Reductions use a
+// fixed order (wavefront shuffle tree, then one block over the per-block
+// partials): results are bit-reproducible.
+#include "dev_common.hpp"
+#include "detag_internal.h"
+
+namespace detag {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename ST>
+__global__ __launch_bounds__(kThreads) void mean_kernel(int n, int64_t d, int64_t ld, const ST *__restrict__ X,
+                                                        float *__restrict__ xbar) {
+  const int64_t c = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  if (c >= d) return;
+  double s = 0.0;
+  for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));
+  xbar[c] = float(s / n);
+}
+
+__device__ __forceinline__ double block_sum(double v) {
+  __shared__ double part[kThreads / 64];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+  if (threadIdx.x == 0)
+    for (int w = 0; w < kThreads / 64; ++w) t += part[w];
+  return t;  // valid in thread 0
+}
+
+template <typename ST>
+__global__ __launch_bounds__(kThreads) void consensus_partial_kernel(int n, int64_t d, int64_t ld,
+                                                                     const ST *__restrict__ X,
+                                                                     double *__restrict__ partials) {
+  const int64_t c = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  double acc = 0.0;
+  if (c < d) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));
+    const double m = s / n;
+    for (int i = 0; i < n; ++i) {
+      const double dev = double(to_f32(X[int64_t(i) * ld + c])) - m;
+      acc += dev * dev;
+    }
+  }
+  const double t = block_sum(acc);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(kThreads) void sum_partials_kernel(int64_t count, const double *__restrict__ partials,
+                                                                double *__restrict__ out) {
+  double acc = 0.0;
+  for (int64_t k = threadIdx.x; k < count; k += kThreads) acc += partials[k];
+  const double t = block_sum(acc);
+  if (threadIdx.x == 0) *out = t;
+}
+
+}  // namespace
+
+int launch_mean(const Shape &s, const void *X, float *xbar, void *stream) {
+  const dim3 grid(ceil_div_i64(s.d, kThreads));
+  auto st = static_cast<hipStream_t>(stream);
+  if (s.bf16)
+    mean_kernel<bf16_t><<<grid, kThreads, 0, st>>>(s.n, s.d, s.ld, static_cast<const bf16_t *>(X), xbar);
+  else
+    mean_kernel<float><<<grid, kThreads, 0, st>>>(s.n, s.d, s.ld, static_cast<const float *>(X), xbar);
+  return hip_rc(hipGetLastError());
+}
+
+int64_t consensus_partials_count(const Shape &s) { return (s.d + kThreads - 1) / kThreads; }
+
+int launch_consensus_error(const Shape &s, const void *X, double *partials, double *out, void *stream) {
+  const int64_t blocks = consensus_partials_count(s);
+  auto st = static_cast<hipStream_t>(stream);
+  if (s.bf16)
+    consensus_partial_kernel<bf16_t><<<dim3(blocks), kThreads, 0, st>>>(s.n, s.d, s.ld,
+                                                                         static_cast<const bf16_t *>(X), partials);
+  else
+    consensus_partial_kernel<float><<<dim3(blocks), kThreads, 0, st>>>(s.n, s.d, s.ld,
+                                                                        static_cast<const float *>(X), partials);
+  int rc = hip_rc(hipGetLastError());
+  if (rc) return rc;
+  sum_partials_kernel<<<1, kThreads, 0, st>>>(blocks, partials, out);
+  return hip_rc(hipGetLastError());
+}
+
+}  // namespace detag

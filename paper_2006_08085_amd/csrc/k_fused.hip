@@ -1,0 +1,261 @@
+// K-round fused DeTAG phase for ring and 2-D torus gossip matrices.
+//
+// Gossip mixes workers (rows) and never columns, so a set of columns together
+// with ALL n rows is a closed system: one lane owns one column, keeps the n
+// worker values of that column in registers, and runs all K rounds of
+// Algorithm 3 there.  The neighbour pattern is a compile-time function of the
+// row index, so every z[j] below is a fixed register.  HBM sees each state
+// element once on the way in and once on the way out, whatever K is:
+//   phase (ATC/ALG2): read X, Y, Gnew, Gold, write X, Y  = 24 B per element (fp32 state)
+//   gossip only     : read Z, write Z                    =  8 B per element
+// A wavefront reads 256 contiguous bytes of one row per load instruction and a
+// 256-thread block 1 KiB; rows are n*ld apart, which the hardware sees as n
+// (times four matrices) sequential streams.
+//
+// Paper: Algorithm 3 (accelerated gossip), Algorithm 2 (phase update) and the
+// matrix form in the proof of Theorem 3.
+#include "dev_common.hpp"
+#include "detag_internal.h"
+
+namespace detag {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int N>
+struct Ring {
+  static constexpr int n = N, deg = 2;
+  __host__ __device__ static constexpr int nb(int i, int k) { return k == 0 ? (i + N - 1) % N : (i + 1) % N; }
+};
+
+template <int R, int C>
+struct Torus {
+  static constexpr int n = R * C, deg = 4;
+  __host__ __device__ static constexpr int nb(int i, int k) {
+    const int r = i / C, c = i % C;
+    return k == 0 ? ((r + R - 1) % R) * C + c
+         : k == 1 ? ((r + 1) % R) * C + c
+         : k == 2 ? r * C + (c + C - 1) % C
+                  : r * C + (c + 1) % C;
+  }
+};
+
+// Coefficients of one round: z_new = a*z_i + b*sum_nb z_j - eta*z_prev_i,
+// a = (1+eta)*w_self, b = (1+eta)*w_nb.
+struct Coef {
+  float a, b, neg_eta, a_first;  // a_first = a - eta: first round, where z_prev = z
+};
+
+template <class T>
+__device__ __forceinline__ float nb_sum(const float (&z)[T::n], int i) {
+  float s = z[T::nb(i, 0)];
+#pragma unroll
+  for (int k = 1; k < T::deg; ++k) s += z[T::nb(i, k)];
+  return s;
+}
+
+// p <- a*z + b*nbsum(z) - eta*p   (p holds z_{r-1} on entry and z_{r+1} on exit)
+template <class T>
+__device__ __forceinline__ void ag_round(const float (&z)[T::n], float (&p)[T::n], const Coef &c) {
+#pragma unroll
+  for (int i = 0; i < T::n; ++i) p[i] = fmaf(c.b, nb_sum<T>(z, i), fmaf(c.a, z[i], c.neg_eta * p[i]));
+}
+
+// K >= 1 rounds starting from z_{-1} = z_0 = u.  Result in u; p is scratch.
+template <class T>
+__device__ __forceinline__ void ag_rounds(float (&u)[T::n], float (&p)[T::n], const Coef &c, int K) {
+#pragma unroll
+  for (int i = 0; i < T::n; ++i) p[i] = fmaf(c.b, nb_sum<T>(u, i), c.a_first * u[i]);  // z_1 in p
+  int r = 1;
+  for (; r + 2 <= K; r += 2) {
+    ag_round<T>(p, u, c);  // z_{r+1} in u
+    ag_round<T>(u, p, c);  // z_{r+2} in p
+  }
+  if (r < K) {
+    ag_round<T>(p, u, c);
+  } else {
+#pragma unroll
+    for (int i = 0; i < T::n; ++i) u[i] = p[i];
+  }
+}
+
+// Register budget: the live state is 2 (gossip only) or 3 (phase) arrays of n
+// floats per lane, plus the loads in flight.  The kernel asks for the matching
+// waves-per-SIMD so the register allocator works against the real budget.
+constexpr int waves_per_simd(int n, int mode) {
+  const int need = n * (mode == 0 ? 2 : 3) + 40;
+  const int w = 512 / need;
+  return w < 1 ? 1 : w > 8 ? 8 : w;
+}
+
+// Rows whose loads are in flight ahead of the row being consumed.  The loads
+// of a tile are issued in row order through a software pipeline of this depth
+// (the scheduling barriers pin that order); left alone, the compiler hoists all
+// 4n loads of the tile to the top and spills.
+constexpr int kRowsAhead = 12;
+
+// Row i of a tile: `valid` columns starting at column `tile` of row i.
+template <typename E>
+__device__ __forceinline__ rsrc_t row_of(const E *base, int64_t tile, int64_t ld, int i, uint32_t valid) {
+  return make_rsrc(base + tile + int64_t(i) * ld, valid * uint32_t(sizeof(E)));
+}
+
+// MODE 0: Z <- M(Z) on X.  MODE 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
+// MODE 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
+template <class T, typename ST, int MODE>
+__global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_structured_kernel(
+    ST *X, ST *Y, const float *__restrict__ Gn, const float *__restrict__ Go, int64_t d, int64_t ld, Coef c,
+    float alpha, int K) {
+  constexpr int N = T::n;
+  constexpr int D = kRowsAhead < N ? kRowsAhead : N;
+  const int64_t tile = int64_t(blockIdx.x) * kThreads;
+  const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
+  const uint32_t so = threadIdx.x * uint32_t(sizeof(ST));  // lane byte offset in a state row
+  const uint32_t go4 = threadIdx.x * 4u;                   // ... in an fp32 row
+  float u[N], p[N];
+  if constexpr (MODE == 0) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) u[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
+    __builtin_amdgcn_sched_barrier(0);
+    ag_rounds<T>(u, p, c, K);
+    __builtin_amdgcn_sched_barrier(0);
+    X = launder_uniform(X);
+#pragma unroll
+    for (int i = 0; i < N; ++i) buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+  } else {
+    float v[N];
+    if constexpr (MODE == 1) {
+      float lx[N], ly[N], lgn[N], lgo[N];
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        lx[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
+        ly[i] = buf_load<ST>(row_of(Y, tile, ld, i, valid), so);
+        lgn[i] = buf_load<float>(row_of(Gn, tile, ld, i, valid), go4);
+        lgo[i] = buf_load<float>(row_of(Go, tile, ld, i, valid), go4);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        if (i + D < N) {
+          lx[i + D] = buf_load<ST>(row_of(X, tile, ld, i + D, valid), so);
+          ly[i + D] = buf_load<ST>(row_of(Y, tile, ld, i + D, valid), so);
+          lgn[i + D] = buf_load<float>(row_of(Gn, tile, ld, i + D, valid), go4);
+          lgo[i + D] = buf_load<float>(row_of(Go, tile, ld, i + D, valid), go4);
+        }
+        u[i] = fmaf(-alpha, ly[i], lx[i]);
+        v[i] = ly[i] + lgn[i] - lgo[i];
+        pin_vgpr(v[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      ag_rounds<T>(u, p, c, K);
+      __builtin_amdgcn_sched_barrier(0);
+      X = launder_uniform(X);
+#pragma unroll
+      for (int i = 0; i < N; ++i) buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+      __builtin_amdgcn_sched_barrier(0);
+      ag_rounds<T>(v, p, c, K);
+      __builtin_amdgcn_sched_barrier(0);
+      Y = launder_uniform(Y);
+#pragma unroll
+      for (int i = 0; i < N; ++i) buf_store<ST>(row_of(Y, tile, ld, i, valid), so, v[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        u[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
+        v[i] = buf_load<ST>(row_of(Y, tile, ld, i, valid), so);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      ag_rounds<T>(v, p, c, K);
+      __builtin_amdgcn_sched_barrier(0);
+      ag_rounds<T>(u, p, c, K);
+      __builtin_amdgcn_sched_barrier(0);
+      // p is free now: the gradient rows are fetched a few rows ahead of the stores
+      X = launder_uniform(X), Y = launder_uniform(Y);
+      float lgn[N], lgo[N];
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        lgn[i] = buf_load<float>(row_of(Gn, tile, ld, i, valid), go4);
+        lgo[i] = buf_load<float>(row_of(Go, tile, ld, i, valid), go4);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        if (i + D < N) {
+          lgn[i + D] = buf_load<float>(row_of(Gn, tile, ld, i + D, valid), go4);
+          lgo[i + D] = buf_load<float>(row_of(Go, tile, ld, i + D, valid), go4);
+        }
+        buf_store<ST>(row_of(X, tile, ld, i, valid), so, fmaf(-alpha, v[i], u[i]));
+        buf_store<ST>(row_of(Y, tile, ld, i, valid), so, v[i] + lgn[i] - lgo[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
+template <class T, typename ST>
+int launch_t(const Shape &s, int mode, void *X, void *Y, const float *Gn, const float *Go, const Coef &c,
+             float alpha, int K, void *stream) {
+  const dim3 grid(ceil_div_i64(s.d, kThreads));
+  auto st = static_cast<hipStream_t>(stream);
+  ST *x = static_cast<ST *>(X), *y = static_cast<ST *>(Y);
+  switch (mode) {
+    case 0: fused_structured_kernel<T, ST, 0><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
+    case 1: fused_structured_kernel<T, ST, 1><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
+    default: fused_structured_kernel<T, ST, 2><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
+  }
+  return hip_rc(hipGetLastError());
+}
+
+template <class T>
+int launch_s(const Shape &s, int mode, void *X, void *Y, const float *Gn, const float *Go, const Coef &c,
+             float alpha, int K, void *stream) {
+  return s.bf16 ? launch_t<T, bf16_t>(s, mode, X, Y, Gn, Go, c, alpha, K, stream)
+                : launch_t<T, float>(s, mode, X, Y, Gn, Go, c, alpha, K, stream);
+}
+
+}  // namespace
+
+bool fused_structured_available(const HostW &W) {
+  if (W.structure == kRing) return W.n == 4 || W.n == 8 || W.n == 16 || W.n == 32 || W.n == 64;
+  if (W.structure == kTorus)
+    return (W.trows == 8 && W.tcols == 8) || (W.trows == 4 && W.tcols == 4) || (W.trows == 4 && W.tcols == 8);
+  return false;
+}
+
+int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, void *Y, const float *Gn,
+                            const float *Go, float alpha, int K, float eta, void *stream) {
+  if (K < 1 || !fused_structured_available(W)) return -1;
+  Coef c;
+  c.a = float((1.0 + double(eta)) * W.w_self);
+  c.b = float((1.0 + double(eta)) * W.w_nb);
+  c.neg_eta = -eta;
+  c.a_first = float((1.0 + double(eta)) * W.w_self - double(eta));
+#define DETAG_GO(T) return launch_s<T>(s, mode, X, Y, Gn, Go, c, alpha, K, stream)
+  if (W.structure == kRing) {
+    switch (W.n) {
+      case 4: DETAG_GO(Ring<4>);
+      case 8: DETAG_GO(Ring<8>);
+      case 16: DETAG_GO(Ring<16>);
+      case 32: DETAG_GO(Ring<32>);
+      case 64: DETAG_GO(Ring<64>);
+    }
+  } else if (W.structure == kTorus) {
+    using T88 = Torus<8, 8>;
+    using T44 = Torus<4, 4>;
+    using T48 = Torus<4, 8>;
+    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
+    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
+    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
+  }
+#undef DETAG_GO
+  return -1;
+}
+
+bool fused_generic_available(const HostW &, const Shape &) { return false; }
+
+int launch_fused_generic(const Shape &, const HostW &, const DevCsr &, int, void *, void *, const float *,
+                         const float *, float, int, float, void *) {
+  return -1;
+}
+
+}  // namespace detag

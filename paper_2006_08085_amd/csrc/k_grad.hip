@@ -1,0 +1,183 @@
+// Local stochastic gradients of the synthetic objectives: the gradient query
+// of Algorithm 2, every worker at its own model.
+//
+//   diagonal quadratic: G = h * (x - b_i) + sigma * z, z standard normal, either
+//     read from an array or regenerated from the counter (seed, step, worker,
+//     column) with Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) and the
+//     Box-Muller transform.  A thread owns the four columns of one Philox block.
+//   least squares: G_i = A_i^T (A_i x_i - b_i), two small passes.
+#include "dev_common.hpp"
+#include "detag_internal.h"
+
+namespace detag {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&out)[4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r) k0 += W0, k1 += W1;
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+  }
+  out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
+}
+
+// 23 random bits plus one half, scaled to (0,1): exact in fp32, never 0 or 1.
+__device__ __forceinline__ float unit_open(uint32_t r) { return (float(r >> 9) + 0.5f) * 0x1p-23f; }
+
+__device__ __forceinline__ void box_muller(uint32_t ra, uint32_t rb, float &z0, float &z1) {
+  const float rad = sqrtf(-2.0f * logf(unit_open(ra)));
+  float s, c;
+  sincospif(2.0f * unit_open(rb), &s, &c);
+  z0 = rad * c;
+  z1 = rad * s;
+}
+
+template <typename ST, bool VEC>
+__global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int64_t ld, const ST *__restrict__ X,
+                                                                  const float *__restrict__ h, int64_t h_row_stride,
+                                                                  const float *__restrict__ b,
+                                                                  const float *__restrict__ noise, float sigma,
+                                                                  uint32_t seed_lo, uint32_t seed_hi, uint32_t step,
+                                                                  float *__restrict__ G) {
+  const int64_t q = int64_t(blockIdx.x) * kThreads + threadIdx.x;  // Philox block = 4 columns
+  const int64_t c0 = q * 4;
+  if (c0 >= d) return;
+  const int i = blockIdx.y;
+  const int valid = int(d - c0 < 4 ? d - c0 : 4);
+  const int64_t off = int64_t(i) * ld + c0;
+  float x[4], hv[4], bv[4], z[4] = {0.f, 0.f, 0.f, 0.f};
+  if (VEC && valid == 4) {
+    if constexpr (sizeof(ST) == 4) {
+      const float4 t = *reinterpret_cast<const float4 *>(X + off);
+      x[0] = t.x, x[1] = t.y, x[2] = t.z, x[3] = t.w;
+    } else {
+      const uint2 t = *reinterpret_cast<const uint2 *>(X + off);
+      x[0] = __uint_as_float(t.x << 16), x[1] = __uint_as_float(t.x & 0xffff0000u);
+      x[2] = __uint_as_float(t.y << 16), x[3] = __uint_as_float(t.y & 0xffff0000u);
+    }
+    const float4 th = *reinterpret_cast<const float4 *>(h + int64_t(i) * h_row_stride + c0);
+    const float4 tb = *reinterpret_cast<const float4 *>(b + off);
+    hv[0] = th.x, hv[1] = th.y, hv[2] = th.z, hv[3] = th.w;
+    bv[0] = tb.x, bv[1] = tb.y, bv[2] = tb.z, bv[3] = tb.w;
+    if (noise) {
+      const float4 tz = *reinterpret_cast<const float4 *>(noise + off);
+      z[0] = tz.x, z[1] = tz.y, z[2] = tz.z, z[3] = tz.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool ok = e < valid;
+      x[e] = ok ? to_f32(X[off + e]) : 0.f;
+      hv[e] = ok ? h[int64_t(i) * h_row_stride + c0 + e] : 0.f;
+      bv[e] = ok ? b[off + e] : 0.f;
+      if (noise) z[e] = ok ? noise[off + e] : 0.f;
+    }
+  }
+  if (!noise && sigma != 0.f) {
+    uint32_t r[4];
+    philox4x32_10(uint32_t(uint64_t(q) & 0xffffffffu), uint32_t(uint64_t(q) >> 32), uint32_t(i), step, seed_lo,
+                  seed_hi, r);
+    box_muller(r[0], r[1], z[0], z[1]);
+    box_muller(r[2], r[3], z[2], z[3]);
+  }
+  float g[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) g[e] = fmaf(sigma, z[e], hv[e] * (x[e] - bv[e]));
+  if (VEC && valid == 4) {
+    *reinterpret_cast<float4 *>(G + off) = make_float4(g[0], g[1], g[2], g[3]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (e < valid) G[off + e] = g[e];
+  }
+}
+
+// resid[i*m + r] = A_i[r,:] . x_i - b_i[r]; one wavefront per (i, r).
+template <typename ST>
+__global__ __launch_bounds__(kThreads) void lstsq_resid_kernel(int n, int m, int64_t d, int64_t ld,
+                                                               const ST *__restrict__ X, const float *__restrict__ A,
+                                                               const float *__restrict__ b,
+                                                               float *__restrict__ resid) {
+  const int64_t row = int64_t(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);  // = i*m + r
+  if (row >= int64_t(n) * m) return;
+  const int i = int(row / m);
+  const int lane = threadIdx.x & 63;
+  const float *a = A + row * d;
+  const ST *x = X + int64_t(i) * ld;
+  float acc = 0.f;
+  for (int64_t c = lane; c < d; c += 64) acc = fmaf(a[c], to_f32(x[c]), acc);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+  if (lane == 0) resid[row] = acc - b[row];
+}
+
+// G[i,c] = sum_r A_i[r,c] * resid[i,r]; one lane per column.
+__global__ __launch_bounds__(kThreads) void lstsq_grad_kernel(int m, int64_t d, int64_t ld,
+                                                              const float *__restrict__ A,
+                                                              const float *__restrict__ resid,
+                                                              float *__restrict__ G) {
+  const int64_t c = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  if (c >= d) return;
+  const int i = blockIdx.y;
+  const float *a = A + int64_t(i) * m * d + c;
+  const float *r = resid + int64_t(i) * m;
+  float acc = 0.f;
+  for (int k = 0; k < m; ++k) acc = fmaf(a[int64_t(k) * d], r[k], acc);
+  G[int64_t(i) * ld + c] = acc;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+int launch_grad_quadratic(const Shape &s, const void *X, const float *h, int h_per_worker, const float *b,
+                          const float *noise, float sigma, uint64_t seed, uint32_t step, float *G, void *stream) {
+  const int64_t blocks4 = (s.d + 3) / 4;
+  const dim3 grid(ceil_div_i64(blocks4, kThreads), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  const int64_t hstride = h_per_worker ? s.ld : 0;
+  const bool vec = s.ld % 4 == 0 && aligned16(h) && aligned16(b) && aligned16(G) && (!noise || aligned16(noise)) &&
+                   (reinterpret_cast<uintptr_t>(X) & (s.bf16 ? 7 : 15)) == 0;
+  const uint32_t slo = uint32_t(seed & 0xffffffffu), shi = uint32_t(seed >> 32);
+#define DETAG_LAUNCH(ST, V)                                                                                     \
+  grad_quadratic_kernel<ST, V><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<const ST *>(X), h, hstride, b, \
+                                                          noise, sigma, slo, shi, step, G)
+  if (s.bf16) {
+    if (vec) DETAG_LAUNCH(bf16_t, true); else DETAG_LAUNCH(bf16_t, false);
+  } else {
+    if (vec) DETAG_LAUNCH(float, true); else DETAG_LAUNCH(float, false);
+  }
+#undef DETAG_LAUNCH
+  return hip_rc(hipGetLastError());
+}
+
+int launch_grad_lstsq(const Shape &s, const void *X, const float *A, const float *b, int m, float *resid, float *G,
+                      void *stream) {
+  auto st = static_cast<hipStream_t>(stream);
+  const int64_t rows = int64_t(s.n) * m;
+  const dim3 g1(ceil_div_i64(rows, kThreads / 64));
+  if (s.bf16)
+    lstsq_resid_kernel<bf16_t><<<g1, kThreads, 0, st>>>(s.n, m, s.d, s.ld, static_cast<const bf16_t *>(X), A, b, resid);
+  else
+    lstsq_resid_kernel<float><<<g1, kThreads, 0, st>>>(s.n, m, s.d, s.ld, static_cast<const float *>(X), A, b, resid);
+  int rc = hip_rc(hipGetLastError());
+  if (rc) return rc;
+  lstsq_grad_kernel<<<dim3(ceil_div_i64(s.d, kThreads), s.n), kThreads, 0, st>>>(m, s.d, s.ld, A, resid, G);
+  return hip_rc(hipGetLastError());
+}
+
+int launch_grad_softmax(const Shape &, const void *, const uint16_t *, const int32_t *, const int32_t *, int, int,
+                        int, int, float *, float *, void *) {
+  return -1;  // provided by k_softmax.hip once built; see detag_grad_softmax_bf16
+}
+
+}  // namespace detag

@@ -1,0 +1,217 @@
+// Streaming kernels: one gossip round over a CSR gossip matrix, the tracker
+// update, the model update, D-PSGD.  Every kernel is a pure pass over n x d
+// elements, d contiguous; threads own VEC adjacent columns and walk the rows,
+// so each lane issues 16-byte (fp32) or 8-byte (bf16) accesses and a wavefront
+// touches 1 KiB (or 512 B) of one row at a time.
+//
+// Paper: the gossip sum is the gossip equation of the "Protocol Layer"
+// subsection; the momentum form is the loop body of Algorithm 3; the tracker
+// and model updates are the end-of-phase lines of Algorithm 2.
+#include "dev_common.hpp"
+#include "detag_internal.h"
+
+namespace detag {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename ST, int VEC>
+__device__ __forceinline__ void load_vec(const ST *p, int valid, float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    if (valid >= 4) {
+      if constexpr (sizeof(ST) == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+      } else {
+        const uint2 t = *reinterpret_cast<const uint2 *>(p);
+        v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
+        v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
+      }
+      return;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) v[e] = e < valid ? to_f32(p[e]) : 0.f;
+}
+
+template <typename ST, int VEC>
+__device__ __forceinline__ void store_vec(ST *p, int valid, const float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    if (valid >= 4) {
+      if constexpr (sizeof(ST) == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+        uint2 t;
+        t.x = uint32_t(bf16_bits_rne(v[0])) | (uint32_t(bf16_bits_rne(v[1])) << 16);
+        t.y = uint32_t(bf16_bits_rne(v[2])) | (uint32_t(bf16_bits_rne(v[3])) << 16);
+        *reinterpret_cast<uint2 *>(p) = t;
+      }
+      return;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e)
+    if (e < valid) p[e] = from_f32<ST>(v[e]);
+}
+
+// out[i,:] = c_mix * sum_k w[k] * cur[col[k],:] + c_prev * prev[i,:]  for rows i in this block's group.
+// With HAS_G: out[i,:] -= alpha * G[i,:] (D-PSGD) and prev is not read.
+template <typename ST, int VEC, bool HAS_G>
+__global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d, int64_t ld,
+                                                                const int32_t *__restrict__ rowptr,
+                                                                const int32_t *__restrict__ colidx,
+                                                                const float *__restrict__ vals,
+                                                                const ST *__restrict__ cur, const ST *prev, ST *out,
+                                                                const float *__restrict__ G, float c_mix,
+                                                                float c_prev, float alpha, int rows_per_group) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int r0 = blockIdx.y * rows_per_group;
+  const int r1 = r0 + rows_per_group < n ? r0 + rows_per_group : n;
+  for (int i = r0; i < r1; ++i) {
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    const int k1 = rowptr[i + 1];
+    for (int k = rowptr[i]; k < k1; ++k) {
+      const float w = vals[k];
+      float v[VEC];
+      load_vec<ST, VEC>(cur + int64_t(colidx[k]) * ld + c0, valid, v);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(w, v[e], acc[e]);
+    }
+    float o[VEC];
+    if constexpr (HAS_G) {
+      float g[VEC];
+      load_vec<float, VEC>(G + int64_t(i) * ld + c0, valid, g);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = fmaf(-alpha, g[e], c_mix * acc[e]);
+    } else {
+      float p[VEC];
+      load_vec<ST, VEC>(prev + int64_t(i) * ld + c0, valid, p);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = fmaf(c_mix, acc[e], c_prev * p[e]);
+    }
+    store_vec<ST, VEC>(out + int64_t(i) * ld + c0, valid, o);
+  }
+}
+
+// mode 0: Y += Gn - Go.   mode 1: X -= alpha*Y (Y before the update); Y += Gn - Go.   mode 2: dst(Y) = src(X) copy.
+template <typename ST, int VEC, int MODE>
+__global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_t ld, ST *X, ST *Y,
+                                                               const float *__restrict__ Gn,
+                                                               const float *__restrict__ Go, float alpha) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int64_t off = int64_t(blockIdx.y) * ld + c0;
+  if constexpr (MODE == 2) {
+    float x[VEC];
+    load_vec<ST, VEC>(X + off, valid, x);
+    store_vec<ST, VEC>(Y + off, valid, x);
+  } else {
+    float y[VEC], gn[VEC], go[VEC];
+    load_vec<ST, VEC>(Y + off, valid, y);
+    load_vec<float, VEC>(Gn + off, valid, gn);
+    load_vec<float, VEC>(Go + off, valid, go);
+    if constexpr (MODE == 1) {
+      float x[VEC];
+      load_vec<ST, VEC>(X + off, valid, x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) x[e] = fmaf(-alpha, y[e], x[e]);
+      store_vec<ST, VEC>(X + off, valid, x);
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) y[e] = y[e] + gn[e] - go[e];
+    store_vec<ST, VEC>(Y + off, valid, y);
+  }
+}
+
+// 16-byte accesses need every row start 16-byte aligned (8 bytes for bf16 vectors of four).
+bool vec_ok(const Shape &s, std::initializer_list<const void *> state_ptrs, std::initializer_list<const void *> f32_ptrs) {
+  if (s.ld % 4) return false;
+  const uintptr_t smask = s.bf16 ? 7 : 15;
+  for (const void *p : state_ptrs)
+    if (p && (reinterpret_cast<uintptr_t>(p) & smask)) return false;
+  for (const void *p : f32_ptrs)
+    if (p && (reinterpret_cast<uintptr_t>(p) & 15)) return false;
+  return true;
+}
+
+int rows_per_group_for(const Shape &s, int col_blocks) {
+  // Enough blocks to fill 256 CUs several times over; one group (all rows in one
+  // block, neighbour re-reads stay in that CU's caches) once columns alone do it.
+  if (col_blocks >= 2048) return s.n;
+  int groups = (2048 + col_blocks - 1) / col_blocks;
+  if (groups > s.n) groups = s.n;
+  return (s.n + groups - 1) / groups;
+}
+
+template <typename ST, bool HAS_G>
+int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, const float *G,
+                   float c_mix, float c_prev, float alpha, void *stream) {
+  const bool vec = vec_ok(s, {cur, prev, out}, {G});
+  const int per_block = kThreads * (vec ? 4 : 1);
+  const int col_blocks = ceil_div_i64(s.d, per_block);
+  const int rpg = rows_per_group_for(s, col_blocks);
+  dim3 grid(col_blocks, (s.n + rpg - 1) / rpg);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    gossip_round_kernel<ST, 4, HAS_G><<<grid, kThreads, 0, st>>>(
+        s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
+        static_cast<ST *>(out), G, c_mix, c_prev, alpha, rpg);
+  else
+    gossip_round_kernel<ST, 1, HAS_G><<<grid, kThreads, 0, st>>>(
+        s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
+        static_cast<ST *>(out), G, c_mix, c_prev, alpha, rpg);
+  return hip_rc(hipGetLastError());
+}
+
+template <typename ST, int MODE>
+int launch_elementwise_t(const Shape &s, void *X, void *Y, const float *Gn, const float *Go, float alpha,
+                         void *stream) {
+  const bool vec = vec_ok(s, {X, Y}, {Gn, Go});
+  const int per_block = kThreads * (vec ? 4 : 1);
+  dim3 grid(ceil_div_i64(s.d, per_block), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    elementwise_kernel<ST, 4, MODE><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X),
+                                                                static_cast<ST *>(Y), Gn, Go, alpha);
+  else
+    elementwise_kernel<ST, 1, MODE><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X),
+                                                                static_cast<ST *>(Y), Gn, Go, alpha);
+  return hip_rc(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float c_mix,
+                        float c_prev, void *stream) {
+  return s.bf16 ? launch_round_t<bf16_t, false>(s, w, cur, prev, out, nullptr, c_mix, c_prev, 0.f, stream)
+                : launch_round_t<float, false>(s, w, cur, prev, out, nullptr, c_mix, c_prev, 0.f, stream);
+}
+
+int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
+                 void *stream) {
+  return s.bf16 ? launch_round_t<bf16_t, true>(s, w, Xin, nullptr, X, G, 1.f, 0.f, alpha, stream)
+                : launch_round_t<float, true>(s, w, Xin, nullptr, X, G, 1.f, 0.f, alpha, stream);
+}
+
+int launch_track(const Shape &s, void *Y, const float *Gn, const float *Go, void *stream) {
+  return s.bf16 ? launch_elementwise_t<bf16_t, 0>(s, nullptr, Y, Gn, Go, 0.f, stream)
+                : launch_elementwise_t<float, 0>(s, nullptr, Y, Gn, Go, 0.f, stream);
+}
+
+int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const float *Go, float alpha,
+                        void *stream) {
+  return s.bf16 ? launch_elementwise_t<bf16_t, 1>(s, X, Y, Gn, Go, alpha, stream)
+                : launch_elementwise_t<float, 1>(s, X, Y, Gn, Go, alpha, stream);
+}
+
+int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream) {
+  return s.bf16 ? launch_elementwise_t<bf16_t, 2>(s, const_cast<void *>(src), dst, nullptr, nullptr, 0.f, stream)
+                : launch_elementwise_t<float, 2>(s, const_cast<void *>(src), dst, nullptr, nullptr, 0.f, stream);
+}
+
+}  // namespace detag

@@ -1,0 +1,171 @@
+"""Host-side tests of the C-ABI library (no GPU needed): it loads, exports every
+declared symbol, builds the gossip matrices the oracle builds, computes the
+same spectrum, and rejects bad input with a status instead of crashing."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2006_08085_amd as D
+from oracle import topology as T
+from workloads import generate as gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(D.LIB_PATH):
+        from paper_2006_08085_amd.build import build
+        build(verbose=False)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "detag.h")).read()
+    declared = set(re.findall(r"\b(detag_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    L = D.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"libdetag.so does not export {name}"
+    assert declared == set(D.EXPORTS)
+    assert D.detag_version().startswith("detag-gfx950")
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 16, 32, 33])
+def test_ring_matches_oracle(n):
+    ctx = D.detag_create(D.Topology.ring(), n, 16)
+    W = T.mixing_matrix(n, gen.edges_ring(n))
+    assert np.allclose(ctx.dense_W(), W, rtol=0, atol=1e-15)
+    l2, ln, lam = T.spectrum(W)
+    s = ctx.spectrum()
+    assert s["lambda2"] == pytest.approx(l2, abs=1e-12)
+    assert s["lambdan"] == pytest.approx(ln, abs=1e-12)
+    assert s["lam"] == pytest.approx(lam, abs=1e-12)
+    assert s["eta"] == pytest.approx(T.eta_from_lambda(lam), abs=1e-12)
+
+
+def test_torus_and_kappa_match_oracle():
+    for kappa in (1.0, 0.1):
+        ctx = D.detag_create(D.Topology.torus(8, 8, kappa=kappa), 64, 16)
+        W = T.slack(T.mixing_matrix(64, gen.edges_torus(8, 8)), kappa)
+        assert np.allclose(ctx.dense_W(), W, rtol=0, atol=1e-15)
+        s = ctx.spectrum()
+        l2, ln, lam = T.spectrum(W)
+        assert (s["lambda2"], s["lambdan"], s["lam"]) == pytest.approx((l2, ln, lam), abs=1e-12)
+        assert s["eta"] == pytest.approx(T.eta_from_lambda(lam), abs=1e-12)
+        assert ctx.has_fused()
+    assert D.detag_create(D.Topology.torus(4, 6), 24, 16).has_fused() is False
+
+
+def test_edge_list_with_metropolis_weights_matches_oracle():
+    e = gen.edges_random_regular(256, 4, seed=0)
+    ctx = D.detag_create(D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), 256, 8)
+    W = T.mixing_matrix(256, e, "metropolis")
+    assert np.allclose(ctx.dense_W(), W, rtol=0, atol=1e-15)
+    assert ctx.spectrum()["lam"] == pytest.approx(T.spectrum(W)[2], abs=1e-12)
+    irregular = np.array([(0, 1), (0, 2), (0, 3), (1, 2), (3, 4)])
+    ctx = D.detag_create(D.Topology.from_edges(irregular, D.DETAG_W_METROPOLIS), 5, 8)
+    W = T.mixing_matrix(5, irregular, "metropolis")
+    assert np.allclose(ctx.dense_W(), W, rtol=0, atol=1e-15)
+    assert ctx.spectrum()["eta"] == pytest.approx(T.eta_from_lambda(T.spectrum(W)[2]), abs=1e-12)
+    with pytest.raises(D.DetagError) as ei:
+        D.detag_create(D.Topology.from_edges(irregular, D.DETAG_W_UNIFORM), 5, 8)
+    assert ei.value.status == D.DETAG_EINVAL
+
+
+def test_library_random_regular_graph_is_valid_by_the_oracles_checks():
+    """The library's own generator: the oracle receives the CSR as data and
+    re-validates it independently (4-regular, simple, symmetric, doubly
+    stochastic, connected) and recomputes lambda and eta."""
+    ctx = D.detag_create(D.Topology.random_regular(4, seed=7), 256, 8)
+    W = ctx.dense_W()
+    T.check_gossip_matrix(W)
+    assert np.array_equal(W, W.T)
+    off = W - np.diag(np.diag(W))
+    assert np.all((off != 0).sum(0) == 4) and np.allclose(off[off != 0], 0.2) and np.allclose(np.diag(W), 0.2)
+    l2, ln, lam = T.spectrum(W)
+    assert lam < 1 - 1e-3
+    s = ctx.spectrum()
+    assert (s["lambda2"], s["lambdan"], s["lam"]) == pytest.approx((l2, ln, lam), abs=1e-12)
+    assert s["eta"] == pytest.approx(T.eta_from_lambda(lam), abs=1e-12)
+    again = D.detag_create(D.Topology.random_regular(4, seed=7), 256, 8).dense_W()
+    other = D.detag_create(D.Topology.random_regular(4, seed=8), 256, 8).dense_W()
+    assert np.array_equal(W, again) and not np.array_equal(W, other)
+
+
+def test_linear_graph_lambda_through_csr():
+    n = 9
+    W = np.zeros((n, n))
+    for i in range(n - 1):
+        W[i, i + 1] = W[i + 1, i] = 0.5
+    W[0, 0] = W[-1, -1] = 0.5
+    ctx = D.detag_create(D.Topology.from_dense(W), n, 4)
+    assert ctx.spectrum()["lam"] == pytest.approx(math.cos(math.pi / n), abs=1e-12)   # Corollary 1
+    assert np.array_equal(ctx.dense_W(), W)
+
+
+def test_asymmetric_W_is_accepted_without_eta():
+    P = np.roll(np.eye(5), 1, axis=1)
+    W = 0.5 * np.eye(5) + 0.5 * P
+    ctx = D.detag_create(D.Topology.from_dense(W), 5, 4)
+    assert np.array_equal(ctx.dense_W(), W)
+    s = ctx.spectrum()
+    assert all(math.isnan(s[k]) for k in ("lambda2", "lambdan", "lam", "eta"))
+
+
+def test_rejections():
+    def status(topo, n=6, d=4, ld=None, dtype=D.DETAG_F32):
+        with pytest.raises(D.DetagError) as ei:
+            D.detag_create(topo, n, d, ld, dtype)
+        assert ei.value.message
+        return ei.value.status
+
+    W = T.mixing_matrix(6, gen.edges_ring(6))
+    bad = W.copy(); bad[0, 0] += 1e-6
+    assert status(D.Topology.from_dense(bad)) == D.DETAG_ENOT_DOUBLY_STOCHASTIC
+    neg = W.copy(); neg[0, 1] = neg[1, 0] = -0.1; neg[0, 0] += 0.1 + 1 / 3; neg[1, 1] += 0.1 + 1 / 3
+    assert status(D.Topology.from_dense(neg)) == D.DETAG_ENOT_DOUBLY_STOCHASTIC
+    two = np.kron(np.eye(2), T.mixing_matrix(3, gen.edges_ring(3)))
+    assert status(D.Topology.from_dense(two)) == D.DETAG_EDISCONNECTED
+    periodic = np.zeros((4, 4))
+    for i in range(4):
+        periodic[i, (i + 1) % 4] = periodic[i, (i - 1) % 4] = 0.5
+    assert status(D.Topology.from_dense(periodic), n=4) == D.DETAG_EDISCONNECTED   # lambda_n = -1
+    assert status(D.Topology.ring(), n=0) == D.DETAG_EINVAL
+    assert status(D.Topology.ring(), d=0) == D.DETAG_EINVAL
+    assert status(D.Topology.ring(), d=8, ld=7) == D.DETAG_EINVAL
+    assert status(D.Topology.ring(kappa=0.0)) == D.DETAG_EINVAL
+    assert status(D.Topology.ring(kappa=1.5)) == D.DETAG_EINVAL
+    assert status(D.Topology.torus(2, 2)) == D.DETAG_EINVAL            # rows*cols != n
+    assert status(D.Topology.random_regular(3, 0)) == D.DETAG_EINVAL   # odd degree
+    assert status(D.Topology.from_edges(np.array([(0, 1), (1, 0)]))) == D.DETAG_EINVAL   # repeated edge
+    assert status(D.Topology.from_edges(np.array([(0, 9)]))) == D.DETAG_EINVAL
+    assert status(D.Topology(kind=99)) == D.DETAG_EINVAL
+    assert status(D.Topology.ring(), dtype=5) == D.DETAG_EINVAL
+
+
+def test_fused_availability_and_path_selection():
+    ring8 = D.detag_create(D.Topology.ring(), 8, 4)
+    assert ring8.has_fused()
+    ring8.set_path(D.DETAG_PATH_FUSED)
+    ring8.set_path(D.DETAG_PATH_PER_ROUND)
+    ring7 = D.detag_create(D.Topology.ring(), 7, 4)
+    if not ring7.has_fused():
+        with pytest.raises(D.DetagError) as ei:
+            ring7.set_path(D.DETAG_PATH_FUSED)
+        assert ei.value.status == D.DETAG_EUNSUPPORTED
+    with pytest.raises(D.DetagError):
+        ring8.set_path(17)
+
+
+def test_device_calls_fail_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    ctx = D.detag_create(D.Topology.ring(), 8, 16)
+    import ctypes as C
+    st = D.lib().detag_gossip_accel(ctx._h, C.c_void_p(4096), 2, -1.0, None)
+    assert st == D.DETAG_EHIP
+    assert b"GPU" in D.lib().detag_last_error(ctx._h)

@@ -111,9 +111,9 @@ def test_normal_noise_layout_and_box_muller():
     assert np.array_equal(N.normal_noise(5, 2, n, sub), z[:, sub])
     # Box-Muller: z0^2 + z1^2 = -2 ln u with u from the first word of the block
     r = N.philox4x32_10((np.uint64(3), 0, 1, 2), (5, 0))        # block q=3 -> columns 12..15, worker 1
-    u0 = ((int(r[0]) >> 8) + 0.5) / 2 ** 24
+    u0 = ((int(r[0]) >> 9) + 0.5) / 2 ** 23
     assert z[1, 12] ** 2 + z[1, 13] ** 2 == pytest.approx(-2 * np.log(u0), rel=1e-12)
-    u3 = ((int(r[3]) >> 8) + 0.5) / 2 ** 24
+    u3 = ((int(r[3]) >> 9) + 0.5) / 2 ** 23
     assert np.arctan2(z[1, 15], z[1, 14]) % (2 * np.pi) == pytest.approx(2 * np.pi * u3, rel=1e-9)
     # different step / worker / seed -> different streams
     assert not np.array_equal(z, N.normal_noise(5, 3, n, np.arange(d)))
