@@ -25,6 +25,22 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PHASE_BYTES_PER_ELEMENT = 24   # fp32: read X, Y, G_new, G_old; write X, Y (independent of K)
 
 
+def measured_traffic():
+    """HBM bytes per launch of the fused phase kernel from the committed rocprofv3
+    counter summary (profiles/fused_step_traffic.json), or None if the kernel
+    sources have changed since those counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "fused_step_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    csrc = os.path.join(ROOT, "paper_2006_08085_amd", "csrc")
+    src = b"".join(open(os.path.join(csrc, f), "rb").read() for f in ("k_fused.hip", "dev_common.hpp"))
+    if hashlib.sha256(src).hexdigest() != rec.get("source_sha256"):
+        return None
+    return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+
+
 def cpu_baseline(cfg, sample_cols: int):
     """The fp64 oracle, as it stands, on the first `sample_cols` columns of the
     same workload (columns are independent for this objective), one step."""
@@ -54,8 +70,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=[2, 4])
-    ap.add_argument("--cpu-sample-cols", type=int, default=262_144)
+    ap.add_argument("--cpu-sample-cols", type=int, default=2_097_152)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain device copies of one n x ld fp32 matrix (a kernel of known "
+                         "traffic, for scaling profiler byte counters); untimed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no cross-GPU code exists); use --gpus 1", file=sys.stderr)
@@ -101,6 +120,11 @@ def main():
 
     for _ in range(args.warmup):
         one_step()
+    if args.calibrate_copy:
+        scratch = torch.empty_like(Ga)
+        for _ in range(3):
+            scratch.copy_(b)          # reads n*ld*4 bytes, writes n*ld*4 bytes
+        del scratch
     torch.cuda.synchronize()
 
     # kernels are launched on torch's current stream, so torch events bracket them
@@ -132,7 +156,7 @@ def main():
                    "finite": finite},
         "roofline": {"bound": "hbm", "kernel": "fused_structured_kernel (detag_step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel_ms": phase_ms,
+                     "traffic": measured_traffic() if args.config == 4 else None, "kernel_ms": phase_ms,
                      "algorithmic_bytes_per_launch": PHASE_BYTES_PER_ELEMENT * n * d},
     }
     if not args.no_cpu_baseline:

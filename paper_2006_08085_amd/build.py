@@ -35,15 +35,18 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True, jobs: int = 8) -> str:
+def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None = None, tag: str = "") -> str:
+    """extra_flags / out / tag exist for experiments: a differently configured
+    library written somewhere else, with its own object directory."""
     hipcc = _hipcc()
-    bdir = os.path.join(ROOT, "_build")
+    lib_out = out or LIB
+    bdir = os.path.join(ROOT, "_build") if not tag else os.path.join(ROOT, "_work", "build" + tag)
     os.makedirs(bdir, exist_ok=True)
     srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
 
     def compile_one(src: str) -> str:
         obj = os.path.join(bdir, src + ".o")
-        cmd = [hipcc, *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra_flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                         if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
@@ -55,15 +58,15 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(compile_one, srcs))
-    tmp = LIB + ".tmp"
+    tmp = lib_out + ".tmp"
     r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", tmp, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib_out)
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {lib_out}")
+    return lib_out
 
 
 if __name__ == "__main__":

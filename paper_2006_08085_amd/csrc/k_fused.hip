@@ -92,7 +92,10 @@ constexpr int waves_per_simd(int n, int mode) {
 // of a tile are issued in row order through a software pipeline of this depth
 // (the scheduling barriers pin that order); left alone, the compiler hoists all
 // 4n loads of the tile to the top and spills.
-constexpr int kRowsAhead = 12;
+#ifndef DETAG_ROWS_AHEAD
+#define DETAG_ROWS_AHEAD 12
+#endif
+constexpr int kRowsAhead = DETAG_ROWS_AHEAD;
 
 // Row i of a tile: `valid` columns starting at column `tile` of row i.
 template <typename E>
