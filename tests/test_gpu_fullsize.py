@@ -1,0 +1,89 @@
+"""Parity at the full benchmark size, in the launch configuration bench.py times:
+n=64, 8x8 torus, d=11,173,962 fp32, K=8, in-kernel counter noise.  Columns are
+independent for this objective, so the oracle recomputes a sample of columns
+exactly (first tile, last ragged tile, tile boundaries, random columns)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_08085_amd as D
+from oracle import gossip as OG
+from oracle import noise as ON
+from oracle import objectives as OO
+from oracle import topology as OT
+from tests.util import TOL_F32, amax, rel_err
+from workloads import CONFIGS, generate as gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(D.LIB_PATH):
+        from paper_2006_08085_amd.build import build
+        build(verbose=False)
+    assert torch.cuda.is_available()
+
+
+def _sample_columns(d, rng):
+    edges = [0, 1, 63, 64, 255, 256, 257, 511, 512, 1023, 1024, 4095, 4096]
+    tail_tile = (d // 256) * 256
+    tail = list(range(tail_tile - 3, d))                       # last full tile's end and the whole ragged tile
+    mid = [k * 256 + o for k in (1000, 20000, 43000) for o in (-1, 0, 1, 255)]
+    rnd = rng.integers(0, d, size=1500).tolist()
+    return np.unique(np.array(edges + tail + mid + rnd, dtype=np.int64))
+
+
+def test_config4_full_size_sampled_columns():
+    cfg = CONFIGS[4]
+    n, d, K, alpha, sigma, seed = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.sigma, cfg.seed
+    ld = D.padded_ld(d)
+    ctx = D.detag_create(D.Topology.torus(8, 8), n, d, ld)
+    assert ctx.has_fused()
+    W = OT.mixing_matrix(n, gen.edges_torus(8, 8))
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    assert ctx.spectrum()["eta"] == pytest.approx(eta, abs=1e-12)
+
+    dev = torch.device(DEV)
+    b = gen.device_normal(n, d, ld, seed, 1, dev, std=cfg.extra["b_std"])
+    h = gen.device_log_uniform(d, ld, seed, 2, dev, cfg.extra["h_lo"], cfg.extra["h_hi"])
+    X = gen.device_normal(n, d, ld, seed, 3, dev)              # a non-trivial state, as in mid-run
+    Y = gen.device_normal(n, d, ld, seed, 4, dev)
+    Gb = gen.device_normal(n, d, ld, seed, 5, dev)             # G_old
+    Ga = D.new_matrix(n, d, ld, device=dev)
+
+    cols = _sample_columns(d, np.random.default_rng(0))
+    idx = torch.from_numpy(cols).to(dev)
+    take = lambda t: t[:, idx].double().cpu().numpy()
+    Xs, Ys, Gos, bs = take(X), take(Y), take(Gb), take(b)
+    hs = h[idx].double().cpu().numpy()
+    pad_before = [t[:, d:].clone() for t in (X, Y)]
+    offset0 = (ctx.mean(Y) - ctx.mean(Gb))[:d].clone()         # mean(Y) - mean(G_old) is invariant
+
+    T = 2
+    for t in range(T):
+        ctx.grad_quadratic_diag(X, h, b, Ga, sigma=sigma, seed=seed, step=t)
+        ctx.step(X, Y, Ga, Gb, alpha, K)
+        Ga, Gb = Gb, Ga
+        Gns = OO.grad_quadratic_diag(Xs, hs, bs, ON.normal_noise(seed, t, n, cols), sigma)
+        if t == 0:
+            S1 = amax(Xs, Ys, Gns, Gos)
+            torch.cuda.synchronize()
+            G_dev = take(Gb)                                    # after the swap Gb holds this step's gradient
+            assert rel_err(G_dev, Gns, S1) < TOL_F32
+        Xs, Ys = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
+        Gos = Gns
+        if t == 0:                                              # one step from identical inputs: entry by entry
+            assert rel_err(take(X), Xs, S1) < TOL_F32
+            assert rel_err(take(Y), Ys, S1) < TOL_F32
+    S = amax(Xs, Ys, Gos)                                       # end of the short run: normwise
+    assert rel_err(take(X), Xs, S, floor=1.0) < TOL_F32
+    assert rel_err(take(Y), Ys, S, floor=1.0) < TOL_F32
+    for t, p in zip((X, Y), pad_before):
+        assert torch.equal(t[:, d:], p)                         # padding columns untouched
+    # a property that holds at any size (proof of Theorem 3): mean(Y) - mean(last gradient) never changes
+    offset = (ctx.mean(Y) - ctx.mean(Gb))[:d]
+    assert (offset - offset0).abs().max().item() < 2e-5
