@@ -22,7 +22,7 @@ struct detag_ctx {
   float *d_vals = nullptr;
   void *scratch[2] = {nullptr, nullptr};  // per-round path: n x ld state matrices
   double *d_partials = nullptr;           // consensus-error partial sums
-  float *d_resid = nullptr;               // least-squares residuals
+  float *d_resid = nullptr;               // gradient scratch: least-squares residuals / softmax residuals
   int64_t resid_count = 0;
   detag_path path = DETAG_PATH_AUTO;
   mutable std::string err;
@@ -61,6 +61,18 @@ detag_status need_scratch(detag_ctx *ctx, int count) {
         return set_err(ctx, DETAG_ENOMEM, "could not allocate the per-round gossip scratch");
       }
     }
+  return DETAG_OK;
+}
+
+detag_status need_grad_scratch(detag_ctx *ctx, int64_t floats) {
+  if (ctx->resid_count >= floats) return DETAG_OK;
+  (void)hipFree(ctx->d_resid);
+  ctx->d_resid = nullptr, ctx->resid_count = 0;
+  if (hipMalloc(reinterpret_cast<void **>(&ctx->d_resid), size_t(floats) * sizeof(float)) != hipSuccess) {
+    (void)hipGetLastError();
+    return set_err(ctx, DETAG_ENOMEM, "could not allocate the gradient scratch");
+  }
+  ctx->resid_count = floats;
   return DETAG_OK;
 }
 
@@ -377,16 +389,7 @@ detag_status detag_grad_lstsq(detag_ctx *ctx, const void *X_dev, const float *A_
   if (detag_status st = check_f32_ptr(ctx, b_dev, "b_dev")) return st;
   if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
   if (m < 1) return set_err(ctx, DETAG_EINVAL, "m must be >= 1");
-  const int64_t need = int64_t(ctx->shape.n) * m;
-  if (ctx->resid_count < need) {
-    (void)hipFree(ctx->d_resid);
-    ctx->d_resid = nullptr, ctx->resid_count = 0;
-    if (hipMalloc(reinterpret_cast<void **>(&ctx->d_resid), size_t(need) * sizeof(float)) != hipSuccess) {
-      (void)hipGetLastError();
-      return set_err(ctx, DETAG_ENOMEM, "could not allocate the residual scratch");
-    }
-    ctx->resid_count = need;
-  }
+  if (detag_status st = need_grad_scratch(ctx, int64_t(ctx->shape.n) * m)) return st;
   const int rc = launch_grad_lstsq(ctx->shape, X_dev, A_dev, b_dev, m, ctx->d_resid, G_dev, stream);
   return rc ? hip_fail(ctx, "least-squares gradient", rc) : DETAG_OK;
 }
@@ -406,9 +409,9 @@ detag_status detag_grad_softmax_bf16(detag_ctx *ctx, const void *X_dev, const ui
     return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient limits: 2 <= C <= 10, F % 32 == 0, B % 32 == 0, B <= 256");
   if (int64_t(C) * F + C != ctx->shape.d)
     return set_err(ctx, DETAG_EINVAL, "d must equal C*F + C");
-  const int rc = launch_grad_softmax(ctx->shape, X_dev, feat_dev, labels_dev, batch_dev, S, F, C, B, G_dev, loss_dev,
-                                     stream);
-  if (rc == -1) return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient kernel is not built");
+  if (detag_status st = need_grad_scratch(ctx, softmax_scratch_floats(ctx->shape.n, C, B))) return st;
+  const int rc = launch_grad_softmax(ctx->shape, X_dev, feat_dev, labels_dev, batch_dev, S, F, C, B, ctx->d_resid,
+                                     G_dev, loss_dev, stream);
   return rc ? hip_fail(ctx, "softmax gradient", rc) : DETAG_OK;
 }
 

@@ -82,8 +82,9 @@ int launch_grad_quadratic(const Shape &s, const void *X, const float *h, int h_p
                           void *stream);
 int launch_grad_lstsq(const Shape &s, const void *X, const float *A, const float *b, int m, float *resid,
                       float *G, void *stream);
+int64_t softmax_scratch_floats(int n, int C, int B);
 int launch_grad_softmax(const Shape &s, const void *X, const uint16_t *feat, const int32_t *labels,
-                        const int32_t *batch, int S, int F, int C, int B, float *G, float *loss,
+                        const int32_t *batch, int S, int F, int C, int B, float *scratch, float *G, float *loss,
                         void *stream);
 
 }  // namespace detag

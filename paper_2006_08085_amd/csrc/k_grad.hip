@@ -175,9 +175,4 @@ int launch_grad_lstsq(const Shape &s, const void *X, const float *A, const float
   return hip_rc(hipGetLastError());
 }
 
-int launch_grad_softmax(const Shape &, const void *, const uint16_t *, const int32_t *, const int32_t *, int, int,
-                        int, int, float *, float *, void *) {
-  return -1;  // provided by k_softmax.hip once built; see detag_grad_softmax_bf16
-}
-
 }  // namespace detag
