@@ -41,6 +41,11 @@ struct DevCsr {
   const int32_t *rowptr = nullptr;  // n+1
   const int32_t *colidx = nullptr;  // nnz
   const float *vals = nullptr;      // nnz, fp32 copies of W_ji
+  // the same matrix with the diagonal split off (for kernels that keep a worker's own value in registers)
+  const int32_t *nb_rowptr = nullptr;  // n+1
+  const int32_t *nb_colidx = nullptr;  // nnz - n
+  const float *nb_vals = nullptr;      // nnz - n
+  const float *w_self = nullptr;       // n
 };
 
 struct Shape {

@@ -48,6 +48,12 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, int(bytes), 0x00020000);
 }
 
+// Row i of a tile: `valid` columns starting at column `tile` of row i.
+template <typename E>
+__device__ __forceinline__ rsrc_t row_of(const E *base, int64_t tile, int64_t ld, int i, uint32_t valid) {
+  return make_rsrc(base + tile + int64_t(i) * ld, valid * uint32_t(sizeof(E)));
+}
+
 // Cache-policy bits of the buffer instructions on gfx950 (the `aux` operand):
 // bit 0 = sc0, bit 1 = nt, bit 4 = sc1.  State tiles are touched exactly once
 // per kernel, so they are streamed with nt (non-temporal).

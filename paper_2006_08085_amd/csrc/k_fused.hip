@@ -97,12 +97,6 @@ constexpr int waves_per_simd(int n, int mode) {
 #endif
 constexpr int kRowsAhead = DETAG_ROWS_AHEAD;
 
-// Row i of a tile: `valid` columns starting at column `tile` of row i.
-template <typename E>
-__device__ __forceinline__ rsrc_t row_of(const E *base, int64_t tile, int64_t ld, int i, uint32_t valid) {
-  return make_rsrc(base + tile + int64_t(i) * ld, valid * uint32_t(sizeof(E)));
-}
-
 // MODE 0: Z <- M(Z) on X.  MODE 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
 // MODE 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
 template <class T, typename ST, int MODE>
@@ -251,13 +245,6 @@ int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, v
     if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
   }
 #undef DETAG_GO
-  return -1;
-}
-
-bool fused_generic_available(const HostW &, const Shape &) { return false; }
-
-int launch_fused_generic(const Shape &, const HostW &, const DevCsr &, int, void *, void *, const float *,
-                         const float *, float, int, float, void *) {
   return -1;
 }
 

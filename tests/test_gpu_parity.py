@@ -390,3 +390,83 @@ def test_errors_are_statuses_not_crashes():
     assert ei.value.status == D.DETAG_EINVAL
     with pytest.raises(ValueError):
         ctx.gossip_accel(torch.zeros(8, 64, device=DEV), 2)   # wrong pitch is caught by the binding
+
+
+# ---------------------------------------------------------------------------
+# on-chip kernel for arbitrary W (n <= 256)
+# ---------------------------------------------------------------------------
+def _irregular_edges(n, seed):
+    rng = np.random.default_rng(seed)
+    e = {(i, i + 1) for i in range(n - 1)}                     # a path keeps it connected
+    while len(e) < 2 * n:
+        a, b = sorted(rng.integers(0, n, 2).tolist())
+        if a != b:
+            e.add((a, b))
+    return np.array(sorted(e), dtype=np.int64)
+
+
+@pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (61, "irregular"), (100, "irregular"), (130, "rr"), (256, "rr")])
+@pytest.mark.parametrize("K", [1, 2, 5, 16])
+def test_generic_fused_gossip_and_step(n, graph, K):
+    d, ld = 150, 160               # two full 64-column tiles and a ragged one
+    if graph == "asym":
+        W = 0.5 * np.eye(n) + 0.5 * np.roll(np.eye(n), 1, axis=1)
+        topo = D.Topology.from_dense(W)
+    else:
+        e = gen.edges_random_regular(n, 4, seed=n) if graph == "rr" else _irregular_edges(n, seed=n)
+        topo, W = D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), OT.mixing_matrix(n, e, "metropolis")
+    ctx = D.detag_create(topo, n, d, ld)
+    assert ctx.has_fused()
+    ctx.set_path(D.DETAG_PATH_FUSED)
+    eta, alpha = eta_for(W), 0.05
+    Z = gen.state(n, d, seed=K)
+    Zd = to_dev(Z, ld)
+    ctx.gossip_accel(Zd, K, eta)
+    assert rel_err(to_host(Zd, d), OG.accelerated_gossip(Z, W, K, eta), amax(Z)) < TOL_F32
+    assert padding_ok(Zd, d)
+    X, Y, Gn, Go = (gen.state(n, d, s) for s in (1, 2, 3, 4))
+    for variant, vcode in (("atc", D.DETAG_VARIANT_ATC), ("alg2", D.DETAG_VARIANT_ALG2)):
+        Xd, Yd, Gnd, God = (to_dev(a, ld) for a in (X, Y, Gn, Go))
+        ctx.step(Xd, Yd, Gnd, God, alpha, K, eta, vcode)
+        Xr, Yr = OG.detag_step(X, Y, Gn, Go, W, alpha, K, eta, variant)
+        S = amax(X, Y, Gn, Go)
+        assert rel_err(to_host(Xd, d), Xr, S) < TOL_F32
+        assert rel_err(to_host(Yd, d), Yr, S) < TOL_F32
+        assert padding_ok(Xd, d) and padding_ok(Yd, d)
+
+
+def test_config5_shape_bf16_short_run():
+    """n=256 random 4-regular graph with Metropolis weights, bf16 X/Y, K=16, lr=0.5,
+    heterogeneous offsets b ~ N(0,4); d reduced to 4,096 columns and 3 steps so
+    the oracle finishes in seconds (columns are independent).  The oracle rounds
+    X and Y to bf16 after every step, as the stored state is."""
+    from workloads import CONFIGS
+    cfg = CONFIGS[5]
+    n, K, alpha = cfg.n, cfg.K, cfg.lr
+    d, T = 4096 + 37, 3
+    ld = D.padded_ld(d)
+    e = gen.edges_random_regular(n, 4, seed=cfg.seed)
+    W = OT.mixing_matrix(n, e, "metropolis")
+    ctx = D.detag_create(D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), n, d, ld, D.DETAG_BF16)
+    eta = ctx.spectrum()["eta"]
+    assert eta == pytest.approx(eta_for(W), abs=1e-12)
+    h, b = gen.quadratic_problem(n, d, seed=cfg.seed, b_std=cfg.extra["b_std"])
+    hd = torch.zeros(ld); hd[:d] = torch.from_numpy(h); hd = hd.to(DEV)
+    bd = to_dev(b, ld)
+    Xd, Yd = (D.new_matrix(n, d, ld, dtype=torch.bfloat16) for _ in range(2))
+    Ga, Gb = D.new_matrix(n, d, ld), D.new_matrix(n, d, ld)
+    X = np.zeros((n, d)); Y = np.zeros((n, d)); Gold = np.zeros((n, d))
+    for t in range(T):
+        ctx.grad_quadratic_diag(Xd, hd, bd, Ga)
+        ctx.step(Xd, Yd, Ga, Gb, alpha, K)
+        Ga, Gb = Gb, Ga
+        Gnew = OO.grad_quadratic_diag(X, h, b)
+        Xn, Yn = OG.detag_step(X, Y, Gnew, Gold, W, alpha, K, eta)
+        if t == 0:      # one step from identical inputs, no intermediate rounding in the oracle
+            S1 = amax(X, Y, Gnew, Gold)
+            assert rel_err(to_host(Xd, d), Xn, S1) < TOL_BF16
+            assert rel_err(to_host(Yd, d), Yn, S1) < TOL_BF16
+        X, Y, Gold = OO.round_bf16(Xn).astype(np.float64), OO.round_bf16(Yn).astype(np.float64), Gnew
+    S = amax(X, Y, Gold)
+    assert rel_err(to_host(Xd, d), X, S, floor=1.0) < TOL_BF16
+    assert rel_err(to_host(Yd, d), Y, S, floor=1.0) < TOL_BF16
