@@ -20,8 +20,10 @@ struct detag_ctx {
   int device = -1;
   int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
   float *d_vals = nullptr;
-  int32_t *d_nb_rowptr = nullptr, *d_nb_colidx = nullptr;  // W with the diagonal split off
-  float *d_nb_vals = nullptr, *d_w_self = nullptr;
+  int32_t *d_ell_col = nullptr;  // fixed-width neighbour lists for the on-chip kernel for arbitrary W
+  float *d_ell_val = nullptr, *d_ell_self = nullptr;
+  int ell_rpt = 0, ell_deg = 0;
+  bool fused_generic = false;             // build_ell succeeded for this W
   void *scratch[2] = {nullptr, nullptr};  // per-round path: n x ld state matrices
   double *d_partials = nullptr;           // consensus-error partial sums
   float *d_resid = nullptr;               // gradient scratch: least-squares residuals / softmax residuals
@@ -95,14 +97,15 @@ detag_status resolve_eta(const detag_ctx *ctx, double eta_in, float *eta_out) {
 DevCsr dev_csr(const detag_ctx *ctx) {
   DevCsr w;
   w.rowptr = ctx->d_rowptr, w.colidx = ctx->d_colidx, w.vals = ctx->d_vals;
-  w.nb_rowptr = ctx->d_nb_rowptr, w.nb_colidx = ctx->d_nb_colidx, w.nb_vals = ctx->d_nb_vals, w.w_self = ctx->d_w_self;
+  w.ell_col = ctx->d_ell_col, w.ell_val = ctx->d_ell_val, w.ell_self = ctx->d_ell_self;
+  w.ell_rpt = ctx->ell_rpt, w.ell_deg = ctx->ell_deg;
   return w;
 }
 
 enum Chosen { kPerRound, kFusedStructured, kFusedGeneric };
 
 detag_status choose_path(const detag_ctx *ctx, Chosen *out) {
-  const bool fs = fused_structured_available(ctx->W), fg = fused_generic_available(ctx->W, ctx->shape);
+  const bool fs = fused_structured_available(ctx->W), fg = ctx->fused_generic;
   if (ctx->path == DETAG_PATH_PER_ROUND) return *out = kPerRound, DETAG_OK;
   if (fs) return *out = kFusedStructured, DETAG_OK;
   if (fg) return *out = kFusedGeneric, DETAG_OK;
@@ -184,6 +187,9 @@ detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int6
   }
   ctx->shape.n = n, ctx->shape.d = d, ctx->shape.ld = ld, ctx->shape.bf16 = state == DETAG_BF16;
 
+  EllHost ell;
+  ctx->fused_generic = build_ell(ctx->W, ell);
+
   int count = 0;
   if (hipGetDeviceCount(&count) != hipSuccess || count < 1) {
     (void)hipGetLastError();
@@ -205,29 +211,14 @@ detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int6
     e = hipMemcpy(ctx->d_rowptr, ctx->W.rowptr.data(), (size_t(n) + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_colidx, ctx->W.colidx.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_vals, vals32.data(), nnz * sizeof(float), hipMemcpyHostToDevice);
-  {  // the same rows without their self term, and the self weights on their own
-    std::vector<int32_t> nrp(1, 0), nci;
-    std::vector<float> nv, ws(n, 0.f);
-    for (int i = 0; i < n; ++i) {
-      for (int k = ctx->W.rowptr[i]; k < ctx->W.rowptr[i + 1]; ++k) {
-        if (ctx->W.colidx[k] == i) ws[i] = vals32[k];
-        else nci.push_back(ctx->W.colidx[k]), nv.push_back(vals32[k]);
-      }
-      nrp.push_back(int32_t(nci.size()));
-    }
-    // the on-chip kernel for arbitrary W walks rows in groups of four up to 256: pad with empty rows
-    while (nrp.size() < 257 + 8) nrp.push_back(nrp.back());
-    if (ws.size() < 256 + 8) ws.resize(256 + 8, 0.f);
-    const size_t m = nci.size() ? nci.size() : 1;  // n = 1 has no neighbours: keep the allocations non-empty
-    nci.resize(m), nv.resize(m);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_nb_rowptr), nrp.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_nb_colidx), m * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_nb_vals), m * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_w_self), ws.size() * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_nb_rowptr, nrp.data(), nrp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_nb_colidx, nci.data(), m * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_nb_vals, nv.data(), m * sizeof(float), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_w_self, ws.data(), ws.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (ctx->fused_generic) {
+    ctx->ell_rpt = ell.rpt, ctx->ell_deg = ell.deg;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_col), ell.col.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_val), ell.val.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_self), ell.self.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_col, ell.col.data(), ell.col.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_val, ell.val.data(), ell.val.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_self, ell.self.data(), ell.self.size() * sizeof(float), hipMemcpyHostToDevice);
   }
   if (e != hipSuccess) {
     const int rc = int(e);
@@ -245,10 +236,9 @@ void detag_destroy(detag_ctx *ctx) {
     (void)hipFree(ctx->d_rowptr);
     (void)hipFree(ctx->d_colidx);
     (void)hipFree(ctx->d_vals);
-    (void)hipFree(ctx->d_nb_rowptr);
-    (void)hipFree(ctx->d_nb_colidx);
-    (void)hipFree(ctx->d_nb_vals);
-    (void)hipFree(ctx->d_w_self);
+    (void)hipFree(ctx->d_ell_col);
+    (void)hipFree(ctx->d_ell_val);
+    (void)hipFree(ctx->d_ell_self);
     (void)hipFree(ctx->d_partials);
     (void)hipFree(ctx->d_resid);
     (void)hipFree(ctx->scratch[0]);
@@ -289,7 +279,7 @@ detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
 
 int32_t detag_has_fused(const detag_ctx *ctx) {
   if (!ctx) return 0;
-  return fused_structured_available(ctx->W) || fused_generic_available(ctx->W, ctx->shape) ? 1 : 0;
+  return fused_structured_available(ctx->W) || ctx->fused_generic ? 1 : 0;
 }
 
 detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double eta, void *stream) {

@@ -41,12 +41,24 @@ struct DevCsr {
   const int32_t *rowptr = nullptr;  // n+1
   const int32_t *colidx = nullptr;  // nnz
   const float *vals = nullptr;      // nnz, fp32 copies of W_ji
-  // the same matrix with the diagonal split off (for kernels that keep a worker's own value in registers)
-  const int32_t *nb_rowptr = nullptr;  // n+1
-  const int32_t *nb_colidx = nullptr;  // nnz - n
-  const float *nb_vals = nullptr;      // nnz - n
-  const float *w_self = nullptr;       // n
+  // the same matrix for the on-chip kernel for arbitrary W: fixed-width neighbour lists (see EllHost)
+  const int32_t *ell_col = nullptr;
+  const float *ell_val = nullptr, *ell_self = nullptr;
+  int ell_rpt = 0, ell_deg = 0;
 };
+
+// Fixed-width neighbour lists in the order the on-chip kernel for arbitrary W walks them: wavefront w
+// (of 4) owns rows w, w+4, ..., its r-th row is i = w + 4r and sits at slot s = w*rpt + r.
+//   self[s]          = W_ii
+//   col[s*deg + k], val[s*deg + k] = k-th off-diagonal term (j, W_ji) of row i,
+// padded with (i, 0) up to deg entries; slots of rows >= n hold (0, 0) and self 0.
+struct EllHost {
+  int rpt = 0, deg = 0;  // rows per wavefront (16, 32 or 64) and list width (2, 4 or 8)
+  std::vector<int32_t> col;
+  std::vector<float> val, self;
+};
+// false if W has more than 256 rows or a row with more than 8 off-diagonal terms.
+bool build_ell(const HostW &W, EllHost &out);
 
 struct Shape {
   int n;

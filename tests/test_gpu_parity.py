@@ -395,14 +395,30 @@ def test_errors_are_statuses_not_crashes():
 # ---------------------------------------------------------------------------
 # on-chip kernel for arbitrary W (n <= 256)
 # ---------------------------------------------------------------------------
-def _irregular_edges(n, seed):
+def _irregular_edges(n, seed, max_deg=8):
     rng = np.random.default_rng(seed)
     e = {(i, i + 1) for i in range(n - 1)}                     # a path keeps it connected
+    deg = np.zeros(n, int); deg[0] = deg[-1] = 1; deg[1:-1] = 2
     while len(e) < 2 * n:
         a, b = sorted(rng.integers(0, n, 2).tolist())
-        if a != b:
-            e.add((a, b))
+        if a != b and (a, b) not in e and deg[a] < max_deg and deg[b] < max_deg:
+            e.add((a, b)); deg[a] += 1; deg[b] += 1
     return np.array(sorted(e), dtype=np.int64)
+
+
+def test_wide_rows_fall_back_to_the_per_round_path():
+    n, d, ld, K = 14, 100, 128, 3                               # a star: the hub has 13 neighbours, more than the on-chip kernel's 8
+    e = np.array([(0, j) for j in range(1, n)])
+    W = OT.mixing_matrix(n, e, "metropolis")
+    ctx = D.detag_create(D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), n, d, ld)
+    assert not ctx.has_fused()
+    with pytest.raises(D.DetagError) as ei:
+        ctx.set_path(D.DETAG_PATH_FUSED)
+    assert ei.value.status == D.DETAG_EUNSUPPORTED
+    Z = gen.state(n, d, seed=1)
+    Zd = to_dev(Z, ld)
+    ctx.gossip_accel(Zd, K)
+    assert rel_err(to_host(Zd, d), OG.accelerated_gossip(Z, W, K, eta_for(W)), amax(Z)) < TOL_F32
 
 
 @pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (61, "irregular"), (100, "irregular"), (130, "rr"), (256, "rr")])
