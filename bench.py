@@ -22,20 +22,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
-PHASE_BYTES_PER_ELEMENT = 24   # fp32: read X, Y, G_new, G_old; write X, Y (independent of K)
+PHASE_BYTES_PER_ELEMENT = 24   # detag_step, fp32: read X, Y, G_new, G_old; write X, Y (independent of K)
+FUSED_BYTES_PER_ELEMENT = 28   # detag_step_quadratic, fp32: read X, Y, G, b; write X, Y, G
 
 
-def measured_traffic():
-    """HBM bytes per launch of the fused phase kernel from the committed rocprofv3
-    counter summary (profiles/fused_step_traffic.json), or None if the kernel
-    sources have changed since those counters were taken."""
+def measured_traffic(fused: bool):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary (profiles/*_traffic.json), or None if the kernel sources have
+    changed since those counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "fused_step_traffic.json")
+    path = os.path.join(ROOT, "profiles", "fused_quadratic_traffic.json" if fused else "fused_step_traffic.json")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
     csrc = os.path.join(ROOT, "paper_2006_08085_amd", "csrc")
-    src = b"".join(open(os.path.join(csrc, f), "rb").read() for f in ("k_fused.hip", "dev_common.hpp"))
+    src = b"".join(open(os.path.join(csrc, f), "rb").read() for f in rec["sources"])
     if hashlib.sha256(src).hexdigest() != rec.get("source_sha256"):
         return None
     return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
@@ -72,6 +73,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=[2, 4])
     ap.add_argument("--cpu-sample-cols", type=int, default=2_097_152)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="run the step as two kernels (detag_grad_quadratic_diag, then detag_step) instead of "
+                         "the single detag_step_quadratic kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of one n x ld fp32 matrix (a kernel of known "
                          "traffic, for scaling profiler byte counters); untimed")
@@ -107,15 +111,23 @@ def main():
     Ga, Gb = D.new_matrix(n, d, ld, device=dev), D.new_matrix(n, d, ld, device=dev)
 
     state = {"t": 0, "Ga": Ga, "Gb": Gb}
+    fused = not args.unfused
 
     def one_step(ev=None):
-        ctx.grad_quadratic_diag(X, h, b, state["Ga"], sigma=sigma, seed=cfg.seed, step=state["t"])
-        if ev is not None:
-            ev[0].record()
-        ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K)
-        if ev is not None:
-            ev[1].record()
-        state["Ga"], state["Gb"] = state["Gb"], state["Ga"]
+        if fused:   # gradient query + phase in one kernel; Ga is the single gradient matrix, updated in place
+            if ev is not None:
+                ev[0].record()
+            ctx.step_quadratic(X, Y, state["Ga"], h, b, alpha, K, sigma=sigma, seed=cfg.seed, step=state["t"])
+            if ev is not None:
+                ev[1].record()
+        else:
+            ctx.grad_quadratic_diag(X, h, b, state["Ga"], sigma=sigma, seed=cfg.seed, step=state["t"])
+            if ev is not None:
+                ev[0].record()
+            ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K)
+            if ev is not None:
+                ev[1].record()
+            state["Ga"], state["Gb"] = state["Gb"], state["Ga"]
         state["t"] += 1
 
     for _ in range(args.warmup):
@@ -137,7 +149,8 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     phase_ms = sum(a.elapsed_time(b_) for a, b_ in evs) / args.steps
-    achieved = PHASE_BYTES_PER_ELEMENT * n * d / (phase_ms * 1e-3) / 1e9
+    bpe = FUSED_BYTES_PER_ELEMENT if fused else PHASE_BYTES_PER_ELEMENT
+    achieved = bpe * n * d / (phase_ms * 1e-3) / 1e9
     xbar = ctx.mean(X)
     finite = bool(torch.isfinite(xbar[:d]).all().item())
 
@@ -152,12 +165,15 @@ def main():
                                f"{'8x8 torus' if cfg.topology == 'torus' else 'ring'}, d={d} fp32 (ld={ld}), "
                                f"K={K} accelerated-gossip rounds of X and Y per step, diagonal quadratic + "
                                f"N(0,{sigma}^2) counter-based noise, lr={alpha}",
-                   "step": "detag_grad_quadratic_diag + detag_step (ATC, fused path)",
+                   "step": "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
+                           else "detag_grad_quadratic_diag + detag_step (ATC, fused K rounds)",
                    "finite": finite},
-        "roofline": {"bound": "hbm", "kernel": "fused_structured_kernel (detag_step)",
+        "roofline": {"bound": "hbm",
+                     "kernel": "fused_quadratic_kernel (detag_step_quadratic)" if fused
+                               else "fused_structured_kernel (detag_step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic() if args.config == 4 else None, "kernel_ms": phase_ms,
-                     "algorithmic_bytes_per_launch": PHASE_BYTES_PER_ELEMENT * n * d},
+                     "traffic": measured_traffic(fused) if args.config == 4 else None, "kernel_ms": phase_ms,
+                     "algorithmic_bytes_per_launch": bpe * n * d},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample_cols, d))

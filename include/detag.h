@@ -201,6 +201,22 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
                                        uint32_t step, float *G_dev, void *stream);
 
 /*
+ * detag_grad_quadratic_diag followed by detag_step (ATC), as one kernel: the
+ * gradient query of Algorithm 2 at the phase-start model and the phase update,
+ *   G+ = h*(X - b) + sigma*z;  X+ = M(X - alpha*Y);  Y+ = M(Y + G+ - G).
+ * G_dev (fp32 n x ld) holds the previous gradient buffer g(k-1) on entry and
+ * g(k) on return, so the caller keeps ONE gradient matrix and does not swap.
+ * h_dev: fp32, length ld, shared by all workers; b_dev: fp32 n x ld; noise is
+ * always the counter-based generator of detag_grad_quadratic_diag (sigma = 0
+ * turns it off).  Results are identical to the two separate calls.
+ * Only for contexts on a ring or 2-D torus with a register-resident kernel and
+ * K >= 1 (DETAG_EUNSUPPORTED otherwise).  X, Y, G, b must not overlap.
+ */
+detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
+                                  const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
+                                  int32_t K, double eta, void *stream);
+
+/*
  * Gradient of f_i(x) = 1/2 ||A_i x - b_i||^2:  G[i,:] = A_i^T (A_i X[i,:] - b_i).
  * A_dev: fp32 n x m x d (row pitch d), b_dev: fp32 n x m, G_dev: fp32 n x ld.
  * Uses a context-owned scratch of n*m floats (allocated on first use).

@@ -31,7 +31,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
            "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step",
-           "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_grad_lstsq",
+           "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
 
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
     L.detag_consensus_error.restype = C.c_int
     L.detag_grad_quadratic_diag.argtypes = [vp, vp, vp, i32, vp, vp, f32, u64, u32, vp, vp]
     L.detag_grad_quadratic_diag.restype = C.c_int
+    L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, vp, f32, u64, u32, f64, i32, f64, vp]
+    L.detag_step_quadratic.restype = C.c_int
     L.detag_grad_lstsq.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     L.detag_grad_lstsq.restype = C.c_int
     L.detag_grad_softmax_bf16.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
@@ -294,6 +296,16 @@ class Context:
                                                     self._mat(b, torch.float32, "b"), npz, sigma, seed, step,
                                                     self._mat(G, torch.float32, "G"), self._stream()))
 
+    def step_quadratic(self, X, Y, G, h, b, alpha: float, K: int, sigma: float = 0.0, seed: int = 0, step: int = 0,
+                       eta: float = -1.0):
+        import torch
+        if h.dtype != torch.float32 or not h.is_cuda or h.dim() != 1 or h.numel() < self.d or not h.is_contiguous():
+            raise ValueError("h must be a contiguous float32 GPU vector of length >= d")
+        self._check(lib().detag_step_quadratic(self._h, self._state(X, "X"), self._state(Y, "Y"),
+                                               self._mat(G, torch.float32, "G"), C.c_void_p(h.data_ptr()),
+                                               self._mat(b, torch.float32, "b"), sigma, seed, step, alpha, K, eta,
+                                               self._stream()))
+
     def grad_lstsq(self, X, A, b, G):
         import torch
         if A.dtype != torch.float32 or not A.is_cuda or not A.is_contiguous() or A.dim() != 3 \
@@ -353,6 +365,8 @@ def detag_mean(ctx: Context, X, out=None): return ctx.mean(X, out)
 def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error(X, out)
 def detag_grad_quadratic_diag(ctx: Context, X, h, b, G, noise=None, sigma=0.0, seed=0, step=0):
     ctx.grad_quadratic_diag(X, h, b, G, noise, sigma, seed, step)
+def detag_step_quadratic(ctx: Context, X, Y, G, h, b, alpha, K, sigma=0.0, seed=0, step=0, eta=-1.0):
+    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma, seed, step, eta)
 def detag_grad_lstsq(ctx: Context, X, A, b, G): ctx.grad_lstsq(X, A, b, G)
 def detag_grad_softmax_bf16(ctx: Context, X, feats, labels, batch, C_classes, G, loss=None):
     ctx.grad_softmax_bf16(X, feats, labels, batch, C_classes, G, loss)

@@ -18,12 +18,14 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdetag.so")
 
-SOURCES = ["topology.cpp", "detag_api.hip", "k_stream.hip", "k_fused.hip", "k_fused_generic.hip",
+SOURCES = ["topology.cpp", "detag_api.hip", "k_stream.hip", "k_fused.hip", "k_fused_quad.hip", "k_fused_generic.hip",
            "k_diag.hip", "k_grad.hip", "k_softmax.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 VALU forms are kept off for every kernel in this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the register-resident kernels rely on full unrolling of their row loops (static register indices)
+         "-mllvm", "-pragma-unroll-threshold=1000000",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

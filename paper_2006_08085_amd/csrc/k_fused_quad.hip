@@ -1,0 +1,142 @@
+// Gradient query and DeTAG phase in one pass, for the diagonal-quadratic
+// objective on ring / 2-D torus gossip matrices:
+//
+//   G+ = h * (X - b) + sigma * z              (gradient query of Algorithm 2, at the phase-start model)
+//   X+ = M(X - alpha*Y),  Y+ = M(Y + G+ - G)  (phase update, matrix form in the proof of Theorem 3)
+//
+// with M the K-step accelerated gossip of Algorithm 3.  The gradient needs X,
+// which the phase loads anyway, so fusing it saves one read of X, one write and
+// one read of the gradient: per element the kernel reads X, Y, G, b and writes
+// X, Y, G (28 B, fp32) where the two separate kernels move 36 B.  G is updated
+// in place: row i of the old gradient is read just before the new one is stored.
+//
+// Same register-resident layout as the plain fused phase (one lane = one
+// column, all n rows in VGPRs).  The Gaussian noise is counter-based; one
+// Philox block yields the four normals of four adjacent columns of one worker,
+// so the four lanes of a quad each generate the block of one of four
+// consecutive rows and exchange the results with two DPP quad permutes (a 4x4
+// transpose): every lane evaluates one block per four rows instead of four.
+#include "detag_internal.h"
+#include "fused_common.hpp"
+#include "noise_dev.hpp"
+
+namespace detag {
+namespace {
+
+using namespace fused;
+
+template <int CTRL>
+__device__ __forceinline__ float quad_perm(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// a[k] = M[j][k] in quad lane j  ->  a[k] = M[k][j]
+__device__ __forceinline__ void quad_transpose(float (&a)[4], unsigned j) {
+  const bool odd = j & 1u, hi = j & 2u;
+  const float t0 = quad_perm<0xB1>(odd ? a[0] : a[1]);  // lanes j ^ 1
+  const float t1 = quad_perm<0xB1>(odd ? a[2] : a[3]);
+  const float c0 = odd ? t0 : a[0], c1 = odd ? a[1] : t0, c2 = odd ? t1 : a[2], c3 = odd ? a[3] : t1;
+  const float s0 = quad_perm<0x4E>(hi ? c0 : c2);       // lanes j ^ 2
+  const float s1 = quad_perm<0x4E>(hi ? c1 : c3);
+  a[0] = hi ? s0 : c0, a[1] = hi ? s1 : c1, a[2] = hi ? c2 : s0, a[3] = hi ? c3 : s1;
+}
+
+template <class T, typename ST>
+__global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadratic_kernel(
+    ST *X, ST *Y, float *G, const float *__restrict__ h, const float *__restrict__ b, int64_t d, int64_t ld, Coef c,
+    float alpha, int K, float sigma, uint32_t seed_lo, uint32_t seed_hi, uint32_t step) {
+  constexpr int N = T::n;
+  static_assert(N % 4 == 0, "rows are processed in groups of four");
+  constexpr int D = kRowsAhead < N ? kRowsAhead : N;
+  const int64_t tile = int64_t(blockIdx.x) * kThreads;
+  const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
+  const uint32_t so = threadIdx.x * uint32_t(sizeof(ST)), fo = threadIdx.x * 4u;
+  const unsigned j = threadIdx.x & 3u;
+  const uint64_t q = uint64_t(tile + threadIdx.x) >> 2;
+  const float hc = buf_load<float>(make_rsrc(h + tile, valid * 4u), fo);
+  float u[N], v[N], p[N];
+  float lx[N], ly[N], lg[N], lb[N];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    lx[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
+    ly[i] = buf_load<ST>(row_of(Y, tile, ld, i, valid), so);
+    lg[i] = buf_load<float>(row_of(G, tile, ld, i, valid), fo);
+    lb[i] = buf_load<float>(row_of(b, tile, ld, i, valid), fo);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  float z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + D < N) {
+      lx[i + D] = buf_load<ST>(row_of(X, tile, ld, i + D, valid), so);
+      ly[i + D] = buf_load<ST>(row_of(Y, tile, ld, i + D, valid), so);
+      lg[i + D] = buf_load<float>(row_of(G, tile, ld, i + D, valid), fo);
+      lb[i + D] = buf_load<float>(row_of(b, tile, ld, i + D, valid), fo);
+    }
+    if ((i & 3) == 0 && sigma != 0.f) {  // noise of rows i..i+3 at this lane's column
+      normal4(q, uint32_t(i) + j, step, seed_lo, seed_hi, z);
+      quad_transpose(z, j);
+    }
+    const float g = fmaf(sigma, z[i & 3], hc * (lx[i] - lb[i]));
+    u[i] = fmaf(-alpha, ly[i], lx[i]);
+    v[i] = ly[i] + g - lg[i];
+    pin_vgpr(v[i]);
+    buf_store<float>(row_of(G, tile, ld, i, valid), fo, g);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  ag_rounds<T>(u, p, c, K);
+  __builtin_amdgcn_sched_barrier(0);
+  X = launder_uniform(X);
+#pragma unroll
+  for (int i = 0; i < N; ++i) buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+  __builtin_amdgcn_sched_barrier(0);
+  ag_rounds<T>(v, p, c, K);
+  __builtin_amdgcn_sched_barrier(0);
+  Y = launder_uniform(Y);
+#pragma unroll
+  for (int i = 0; i < N; ++i) buf_store<ST>(row_of(Y, tile, ld, i, valid), so, v[i]);
+}
+
+template <class T>
+int launch_s(const Shape &s, void *X, void *Y, float *G, const float *h, const float *b, const Coef &c, float alpha,
+             int K, float sigma, uint64_t seed, uint32_t step, void *stream) {
+  const dim3 grid(ceil_div_i64(s.d, kThreads));
+  auto st = static_cast<hipStream_t>(stream);
+  const uint32_t slo = uint32_t(seed & 0xffffffffu), shi = uint32_t(seed >> 32);
+  if (s.bf16)
+    fused_quadratic_kernel<T, bf16_t><<<grid, kThreads, 0, st>>>(static_cast<bf16_t *>(X), static_cast<bf16_t *>(Y), G,
+                                                                 h, b, s.d, s.ld, c, alpha, K, sigma, slo, shi, step);
+  else
+    fused_quadratic_kernel<T, float><<<grid, kThreads, 0, st>>>(static_cast<float *>(X), static_cast<float *>(Y), G, h,
+                                                                b, s.d, s.ld, c, alpha, K, sigma, slo, shi, step);
+  return hip_rc(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_fused_quadratic(const Shape &s, const HostW &W, void *X, void *Y, float *G, const float *h, const float *b,
+                           float alpha, int K, float eta, float sigma, uint64_t seed, uint32_t step, void *stream) {
+  if (K < 1 || !fused_structured_available(W)) return -1;
+  const Coef c = make_coef(W, eta);
+#define DETAG_GO(T) return launch_s<T>(s, X, Y, G, h, b, c, alpha, K, sigma, seed, step, stream)
+  if (W.structure == kRing) {
+    switch (W.n) {
+      case 4: DETAG_GO(Ring<4>);
+      case 8: DETAG_GO(Ring<8>);
+      case 16: DETAG_GO(Ring<16>);
+      case 32: DETAG_GO(Ring<32>);
+      case 64: DETAG_GO(Ring<64>);
+    }
+  } else if (W.structure == kTorus) {
+    using T88 = Torus<8, 8>;
+    using T44 = Torus<4, 4>;
+    using T48 = Torus<4, 8>;
+    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
+    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
+    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
+  }
+#undef DETAG_GO
+  return -1;
+}
+
+}  // namespace detag

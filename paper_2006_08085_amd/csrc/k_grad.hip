@@ -6,40 +6,14 @@
 //     column) with Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) and the
 //     Box-Muller transform.  A thread owns the four columns of one Philox block.
 //   least squares: G_i = A_i^T (A_i x_i - b_i), two small passes.
-#include "dev_common.hpp"
 #include "detag_internal.h"
+#include "dev_common.hpp"
+#include "noise_dev.hpp"
 
 namespace detag {
 namespace {
 
 constexpr int kThreads = 256;
-
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                              uint32_t k1, uint32_t (&out)[4]) {
-  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    if (r) k0 += W0, k1 += W1;
-    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
-    c0 = hi1 ^ c1 ^ k0;
-    c1 = lo1;
-    c2 = hi0 ^ c3 ^ k1;
-    c3 = lo0;
-  }
-  out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
-}
-
-// 23 random bits plus one half, scaled to (0,1): exact in fp32, never 0 or 1.
-__device__ __forceinline__ float unit_open(uint32_t r) { return (float(r >> 9) + 0.5f) * 0x1p-23f; }
-
-__device__ __forceinline__ void box_muller(uint32_t ra, uint32_t rb, float &z0, float &z1) {
-  const float rad = sqrtf(-2.0f * logf(unit_open(ra)));
-  float s, c;
-  sincospif(2.0f * unit_open(rb), &s, &c);
-  z0 = rad * c;
-  z1 = rad * s;
-}
 
 template <typename ST, bool VEC>
 __global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int64_t ld, const ST *__restrict__ X,
@@ -83,11 +57,7 @@ __global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int
     }
   }
   if (!noise && sigma != 0.f) {
-    uint32_t r[4];
-    philox4x32_10(uint32_t(uint64_t(q) & 0xffffffffu), uint32_t(uint64_t(q) >> 32), uint32_t(i), step, seed_lo,
-                  seed_hi, r);
-    box_muller(r[0], r[1], z[0], z[1]);
-    box_muller(r[2], r[3], z[2], z[3]);
+    normal4(uint64_t(q), uint32_t(i), step, seed_lo, seed_hi, z);
   }
   float g[4];
 #pragma unroll

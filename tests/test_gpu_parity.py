@@ -486,3 +486,65 @@ def test_config5_shape_bf16_short_run():
     S = amax(X, Y, Gold)
     assert rel_err(to_host(Xd, d), X, S, floor=1.0) < TOL_BF16
     assert rel_err(to_host(Yd, d), Y, S, floor=1.0) < TOL_BF16
+
+
+# ---------------------------------------------------------------------------
+# gradient query + phase in one kernel
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 16), ("torus48", 32), ("torus88", 64)])
+@pytest.mark.parametrize("sigma", [0.0, 0.1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma, dtype):
+    d, ld, K, alpha, seed = 777, 832, 5, 0.5, 99
+    bf = dtype == "bf16"
+    tdt = torch.bfloat16 if bf else torch.float32
+    ctx, W = make_ctx(kind, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    eta = eta_for(W)
+    h, b = gen.quadratic_problem(n, d, seed=3)
+    X, Y, Go = gen.state(n, d, 1), gen.state(n, d, 2), gen.state(n, d, 3)
+    if bf:
+        X, Y = OO.round_bf16(X), OO.round_bf16(Y)
+    hd = torch.full((ld,), SENTINEL); hd[:d] = torch.from_numpy(h); hd = hd.to(DEV)
+    bd = to_dev(b, ld)
+    cols = np.arange(d)
+    # fused
+    Xf, Yf, Gf = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld)
+    # separate calls
+    Xs, Ys, Gos, Gns = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld), to_dev(np.zeros((n, d)), ld)
+    Xr, Yr, Gor = X.astype(np.float64), Y.astype(np.float64), Go.astype(np.float64)
+    for t in range(2):
+        ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=t)
+        ctx.grad_quadratic_diag(Xs, hd, bd, Gns, sigma=sigma, seed=seed, step=t)
+        ctx.step(Xs, Ys, Gns, Gos, alpha, K)
+        Gos, Gns = Gns, Gos
+        noise = ON.normal_noise(seed, t, n, cols) if sigma else None
+        Gn = OO.grad_quadratic_diag(Xr, h, b, noise, sigma)
+        if t == 0:
+            S = amax(Xr, Yr, Gn, Gor)
+            Xn, Yn = OG.detag_step(Xr, Yr, Gn, Gor, W, alpha, K, eta)
+            tol = TOL_BF16 if bf else TOL_F32
+            assert rel_err(to_host(Gf, d), Gn, S) < TOL_F32
+            assert rel_err(to_host(Xf, d), Xn, S) < tol
+            assert rel_err(to_host(Yf, d), Yn, S) < tol
+        # same arithmetic as the two separate kernels: bit-identical state and gradient, both steps
+        torch.cuda.synchronize()
+        assert torch.equal(Xf, Xs) and torch.equal(Yf, Ys) and torch.equal(Gf, Gos)
+        Xr, Yr, Gor = to_host(Xf, d), to_host(Yf, d), to_host(Gf, d)
+    assert padding_ok(Xf, d) and padding_ok(Yf, d) and padding_ok(Gf, d)
+
+
+def test_step_quadratic_unsupported_cases_are_statuses():
+    ctx, _ = make_ctx("rr", 12, 100, 128)
+    X, Y, Gm, b = (D.new_matrix(12, 100, 128) for _ in range(4))
+    h = torch.ones(128, device=DEV)
+    with pytest.raises(D.DetagError) as ei:
+        ctx.step_quadratic(X, Y, Gm, h, b, 0.1, 4)
+    assert ei.value.status == D.DETAG_EUNSUPPORTED
+    ctx2, _ = make_ctx("ring", 8, 100, 128)
+    X, Y, Gm, b = (D.new_matrix(8, 100, 128) for _ in range(4))
+    with pytest.raises(D.DetagError) as ei:
+        ctx2.step_quadratic(X, Y, Gm, h, b, 0.1, 0)
+    assert ei.value.status == D.DETAG_EUNSUPPORTED
+    with pytest.raises(D.DetagError) as ei:
+        ctx2.step_quadratic(X, X, Gm, h, b, 0.1, 2)
+    assert ei.value.status == D.DETAG_EINVAL
