@@ -27,7 +27,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          # the register-resident kernels rely on full unrolling of their row loops (static register indices)
          "-mllvm", "-pragma-unroll-threshold=1000000",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-I", os.path.join(ROOT, "include")]
 
 
 def _hipcc() -> str:
@@ -37,9 +37,12 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None = None, tag: str = "") -> str:
-    """extra_flags / out / tag exist for experiments: a differently configured
-    library written somewhere else, with its own object directory."""
+def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None = None, tag: str = "",
+          csrc: str | None = None) -> str:
+    """extra_flags / out / tag / csrc exist for experiments: a differently configured
+    library (or one from another source directory) written somewhere else, with its
+    own object directory."""
+    CSRC = csrc or globals()["CSRC"]
     hipcc = _hipcc()
     lib_out = out or LIB
     bdir = os.path.join(ROOT, "_build") if not tag else os.path.join(ROOT, "_work", "build" + tag)
@@ -48,7 +51,7 @@ def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None =
 
     def compile_one(src: str) -> str:
         obj = os.path.join(bdir, src + ".o")
-        cmd = [hipcc, *FLAGS, *extra_flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, "-I", CSRC, *extra_flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                         if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
