@@ -20,9 +20,9 @@ struct detag_ctx {
   int device = -1;
   int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
   float *d_vals = nullptr;
-  int32_t *d_ell_col = nullptr;  // fixed-width neighbour lists for the on-chip kernel for arbitrary W
-  float *d_ell_val = nullptr, *d_ell_self = nullptr;
-  int ell_rpt = 0, ell_deg = 0;
+  uint32_t *d_ell_table = nullptr;  // neighbour table of the on-chip kernel for arbitrary W
+  int ell_deg = 0;
+  bool ell_uniform = false;
   bool fused_generic = false;             // build_ell succeeded for this W
   void *scratch[2] = {nullptr, nullptr};  // per-round path: n x ld state matrices
   double *d_partials = nullptr;           // consensus-error partial sums
@@ -97,8 +97,7 @@ detag_status resolve_eta(const detag_ctx *ctx, double eta_in, float *eta_out) {
 DevCsr dev_csr(const detag_ctx *ctx) {
   DevCsr w;
   w.rowptr = ctx->d_rowptr, w.colidx = ctx->d_colidx, w.vals = ctx->d_vals;
-  w.ell_col = ctx->d_ell_col, w.ell_val = ctx->d_ell_val, w.ell_self = ctx->d_ell_self;
-  w.ell_rpt = ctx->ell_rpt, w.ell_deg = ctx->ell_deg;
+  w.ell_table = ctx->d_ell_table, w.ell_deg = ctx->ell_deg, w.ell_uniform = ctx->ell_uniform;
   return w;
 }
 
@@ -212,13 +211,10 @@ detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int6
   if (e == hipSuccess) e = hipMemcpy(ctx->d_colidx, ctx->W.colidx.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(ctx->d_vals, vals32.data(), nnz * sizeof(float), hipMemcpyHostToDevice);
   if (ctx->fused_generic) {
-    ctx->ell_rpt = ell.rpt, ctx->ell_deg = ell.deg;
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_col), ell.col.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_val), ell.val.size() * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_self), ell.self.size() * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_col, ell.col.data(), ell.col.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_val, ell.val.data(), ell.val.size() * sizeof(float), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_self, ell.self.data(), ell.self.size() * sizeof(float), hipMemcpyHostToDevice);
+    ctx->ell_deg = ell.deg, ctx->ell_uniform = ell.uniform;
+    const size_t bytes = ell.table.size() * sizeof(uint32_t);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ctx->d_ell_table), bytes);
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_ell_table, ell.table.data(), bytes, hipMemcpyHostToDevice);
   }
   if (e != hipSuccess) {
     const int rc = int(e);
@@ -236,9 +232,7 @@ void detag_destroy(detag_ctx *ctx) {
     (void)hipFree(ctx->d_rowptr);
     (void)hipFree(ctx->d_colidx);
     (void)hipFree(ctx->d_vals);
-    (void)hipFree(ctx->d_ell_col);
-    (void)hipFree(ctx->d_ell_val);
-    (void)hipFree(ctx->d_ell_self);
+    (void)hipFree(ctx->d_ell_table);
     (void)hipFree(ctx->d_partials);
     (void)hipFree(ctx->d_resid);
     (void)hipFree(ctx->scratch[0]);

@@ -41,21 +41,21 @@ struct DevCsr {
   const int32_t *rowptr = nullptr;  // n+1
   const int32_t *colidx = nullptr;  // nnz
   const float *vals = nullptr;      // nnz, fp32 copies of W_ji
-  // the same matrix for the on-chip kernel for arbitrary W: fixed-width neighbour lists (see EllHost)
-  const int32_t *ell_col = nullptr;
-  const float *ell_val = nullptr, *ell_self = nullptr;
-  int ell_rpt = 0, ell_deg = 0;
+  // the same matrix for the on-chip kernel for arbitrary W: one packed record per row (see EllHost)
+  const uint32_t *ell_table = nullptr;
+  int ell_deg = 0;
+  bool ell_uniform = false;
 };
 
-// Fixed-width neighbour lists in the order the on-chip kernel for arbitrary W walks them: wavefront w
-// (of 4) owns rows w, w+4, ..., its r-th row is i = w + 4r and sits at slot s = w*rpt + r.
-//   self[s]          = W_ii
-//   col[s*deg + k], val[s*deg + k] = k-th off-diagonal term (j, W_ji) of row i,
-// padded with (i, 0) up to deg entries; slots of rows >= n hold (0, 0) and self 0.
+// Neighbour table of the on-chip kernel for arbitrary W (256 row slots, wavefront-major: row i sits at slot
+// (i % 16) * 16 + i / 16).  Per slot: deg/2 words of packed 16-bit LDS byte offsets of the neighbours' rows, then
+// the off-diagonal weights as fp32 bit patterns (one word if every row has equal off-diagonal weights, else deg
+// words), then W_ii.  Missing neighbours point at the row itself with weight 0 (general) or are folded into the
+// self weight (uniform).
 struct EllHost {
-  int rpt = 0, deg = 0;  // rows per wavefront (16, 32 or 64) and list width (2, 4 or 8)
-  std::vector<int32_t> col;
-  std::vector<float> val, self;
+  int deg = 0;            // table width: 2, 4 or 8
+  bool uniform = false;   // each row's off-diagonal weights are all equal
+  std::vector<uint32_t> table;
 };
 // false if W has more than 256 rows or a row with more than 8 off-diagonal terms.
 bool build_ell(const HostW &W, EllHost &out);

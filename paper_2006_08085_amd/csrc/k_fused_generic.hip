@@ -2,74 +2,90 @@
 // 256 workers and at most 8 neighbours per worker (e.g. a random regular graph
 // with Metropolis weights).
 //
-// A block owns 64 columns and all n rows of them.  Wavefront w owns the rows
-// w, w+4, w+8, ...; lane l owns column l.  Each lane keeps z_r and z_{r-1} of its
-// own rows in registers; z_r of ALL rows also sits in LDS (rows x 64 fp32), where
-// the neighbours of a row are read.  Row indices are wavefront-uniform and the
-// neighbour lists have a fixed width, so they arrive through independent scalar
-// loads the compiler can batch, and every LDS access is 64 consecutive words.
-// One round = read the neighbours from LDS, barrier, write the new value back,
-// barrier.  HBM sees the state once per phase (the ATC phase reads Y twice:
-// 18 B instead of 16 B per element with bf16 state); the kernel is bound by LDS
-// bandwidth, (deg+1) words per output per round.
+// A block of 16 wavefronts owns 64 columns and all n rows of them.  Wavefront w
+// owns the rows w, w+16, w+32, ... (16 of them); lane l owns column l.  Each lane
+// keeps z_r and z_{r-1} of its own 16 rows in registers; z_r of ALL rows also
+// sits in LDS (256 x 64 fp32),
+// where the neighbours of a row are read.  Row indices are wavefront-uniform:
+// the neighbour list of a row is a handful of scalars (16-bit LDS offsets packed
+// in pairs, the weights), read once per kernel, and every LDS access is 64
+// consecutive words, free of bank conflicts.  One round = read the neighbours
+// from LDS, barrier, write the new values back, barrier.  HBM sees the state
+// once per phase (the ATC phase reads Y twice: 18 B instead of 16 B per element
+// with bf16 state); the kernel is bound by LDS bandwidth and VALU issue,
+// (deg+1) LDS words and about 3*deg VALU operations per output per round.
 //
 // Paper: Algorithm 3 (accelerated gossip) and Algorithm 2 / the matrix form in
 // the proof of Theorem 3 (phase update).
-#include "dev_common.hpp"
 #include "detag_internal.h"
+#include "dev_common.hpp"
 
 namespace detag {
 namespace {
 
-constexpr int kThreads = 256, kWaves = 4, kCols = 64;
+constexpr int kWaves = 16, kThreads = 64 * kWaves, kCols = 64, kRpt = 16, kRowsMax = kWaves * kRpt;  // 256 rows
 
-struct Ell {
-  const int32_t *col;
-  const float *val, *self;
+// Table words per row: DEG/2 words of packed 16-bit LDS byte offsets, then the
+// neighbour weights (one word if they are all equal, else DEG), then W_ii.
+constexpr int table_stride(int deg, bool uniform) { return deg / 2 + (uniform ? 1 : deg) + 1; }
+
+template <int DEG, bool UNI>
+struct RowTab {
+  uint32_t w[table_stride(DEG, UNI)];
+  __device__ __forceinline__ uint32_t off(int k) const { return (k & 1) ? w[k >> 1] >> 16 : w[k >> 1] & 0xffffu; }
+  __device__ __forceinline__ float val(int k) const { return __uint_as_float(w[DEG / 2 + (UNI ? 0 : k)]); }
+  __device__ __forceinline__ float self() const { return __uint_as_float(w[table_stride(DEG, UNI) - 1]); }
 };
 
-// p <- (1+eta) * (w_self*z_own + sum_k w_k * lds[j_k]) - eta * p, for this lane's rows; then publish p.
-template <int RPT, int DEG>
-__device__ __forceinline__ void round_step(const float (&z)[RPT], float (&p)[RPT], float *lds, int w, int lane,
-                                           const Ell &g, float cm, float neg_eta) {
+// p <- (1+eta) * (W_ii*z_own + sum_k W_ji * lds[j]) - eta * p, for this lane's rows; then publish p.
+template <int DEG, bool UNI>
+__device__ __forceinline__ void round_step(const float (&z)[kRpt], float (&p)[kRpt], const char *lds_b, float *lds,
+                                           int w, int lane, const RowTab<DEG, UNI> (&tab)[kRpt], float cm,
+                                           float neg_eta) {
+  const uint32_t lane4 = uint32_t(lane) * 4u;
 #pragma unroll
-  for (int r = 0; r < RPT; ++r) {
-    const int s = w * RPT + r;
-    float acc = g.self[s] * z[r];
+  for (int r = 0; r < kRpt; ++r) {
+    float acc;
+    if constexpr (UNI) {
+      float s = *reinterpret_cast<const float *>(lds_b + (tab[r].off(0) + lane4));
 #pragma unroll
-    for (int k = 0; k < DEG; ++k) acc = fmaf(g.val[s * DEG + k], lds[g.col[s * DEG + k] * kCols + lane], acc);
+      for (int k = 1; k < DEG; ++k) s += *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4));
+      acc = fmaf(tab[r].val(0), s, tab[r].self() * z[r]);
+    } else {
+      acc = tab[r].self() * z[r];
+#pragma unroll
+      for (int k = 0; k < DEG; ++k)
+        acc = fmaf(tab[r].val(k), *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4)), acc);
+    }
     p[r] = fmaf(cm, acc, neg_eta * p[r]);
   }
   __syncthreads();  // every read of z_r is done
 #pragma unroll
-  for (int r = 0; r < RPT; ++r) lds[(w + kWaves * r) * kCols + lane] = p[r];
+  for (int r = 0; r < kRpt; ++r) lds[(w + kWaves * r) * kCols + lane] = p[r];
   __syncthreads();  // z_{r+1} is visible
 }
 
-template <int RPT>
-__device__ __forceinline__ void publish(const float (&cur)[RPT], float *lds, int w, int lane) {
-#pragma unroll
-  for (int r = 0; r < RPT; ++r) lds[(w + kWaves * r) * kCols + lane] = cur[r];
-  __syncthreads();
-}
-
 // K >= 1 rounds from z_{-1} = z_0 = cur.  Result in cur; prev is scratch.
-template <int RPT, int DEG>
-__device__ __forceinline__ void gossip(float (&cur)[RPT], float (&prev)[RPT], float *lds, int w, int lane,
-                                       const Ell &g, float eta, int K) {
+template <int DEG, bool UNI>
+__device__ __forceinline__ void gossip(float (&cur)[kRpt], float (&prev)[kRpt], float *lds, int w, int lane,
+                                       const RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
   const float cm = 1.f + eta, neg_eta = -eta;
-  publish<RPT>(cur, lds, w, lane);
+  const char *lds_b = reinterpret_cast<const char *>(lds);
 #pragma unroll
-  for (int r = 0; r < RPT; ++r) prev[r] = cur[r];
+  for (int r = 0; r < kRpt; ++r) {
+    lds[(w + kWaves * r) * kCols + lane] = cur[r];
+    prev[r] = cur[r];
+  }
+  __syncthreads();
   int r = 0;
   for (; r + 2 <= K; r += 2) {
-    round_step<RPT, DEG>(cur, prev, lds, w, lane, g, cm, neg_eta);
-    round_step<RPT, DEG>(prev, cur, lds, w, lane, g, cm, neg_eta);
+    round_step<DEG, UNI>(cur, prev, lds_b, lds, w, lane, tab, cm, neg_eta);
+    round_step<DEG, UNI>(prev, cur, lds_b, lds, w, lane, tab, cm, neg_eta);
   }
   if (r < K) {
-    round_step<RPT, DEG>(cur, prev, lds, w, lane, g, cm, neg_eta);
+    round_step<DEG, UNI>(cur, prev, lds_b, lds, w, lane, tab, cm, neg_eta);
 #pragma unroll
-    for (int q = 0; q < RPT; ++q) cur[q] = prev[q];
+    for (int q = 0; q < kRpt; ++q) cur[q] = prev[q];
   }
 }
 
@@ -81,129 +97,150 @@ __device__ __forceinline__ rsrc_t win(const E *base, int64_t tile, int64_t ld, i
 
 // mode 0: Z <- M(Z) on X.  mode 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
 // mode 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
-template <typename ST, int RPT, int DEG>
-__global__ __launch_bounds__(kThreads, 2) void fused_generic_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
-                                                                    const float *__restrict__ Go, int n, int64_t d,
-                                                                    int64_t ld, Ell g, float eta, float alpha, int K,
-                                                                    int mode) {
-  extern __shared__ float lds[];  // (4*RPT) x 64
+template <typename ST, int DEG, bool UNI>
+__global__ __launch_bounds__(kThreads) void fused_generic_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
+                                                                 const float *__restrict__ Go, int n, int64_t d,
+                                                                 int64_t ld, const uint32_t *__restrict__ table,
+                                                                 float eta, float alpha, int K, int mode) {
+  extern __shared__ float lds[];  // 256 x 64
   // the wavefront index is uniform: say so, or the row indices and with them every
-  // neighbour-list access are treated as per-lane values
+  // table access are treated as per-lane values
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int64_t tile = int64_t(blockIdx.x) * kCols;
   const uint32_t valid = uint32_t(d - tile < kCols ? d - tile : kCols);
   const uint32_t so = lane * uint32_t(sizeof(ST)), fo = lane * 4u;
-  float cur[RPT], prev[RPT];
+  constexpr int TS = table_stride(DEG, UNI);
+  RowTab<DEG, UNI> tab[kRpt];
+#pragma unroll
+  for (int r = 0; r < kRpt; ++r)
+#pragma unroll
+    for (int q = 0; q < TS; ++q) tab[r].w[q] = table[(w * kRpt + r) * TS + q];
+  float cur[kRpt], prev[kRpt];
+  auto row = [&](int r) { return w + kWaves * r; };
   if (mode == 0) {
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) cur[r] = buf_load<ST>(win(X, tile, ld, w + kWaves * r, n, valid), so);
-    gossip<RPT, DEG>(cur, prev, lds, w, lane, g, eta, K);
+    for (int r = 0; r < kRpt; ++r) cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) buf_store<ST>(win(X, tile, ld, w + kWaves * r, n, valid), so, cur[r]);
+    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
   } else if (mode == 1) {
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-      const int i = w + kWaves * r;
-      cur[r] = fmaf(-alpha, buf_load<ST>(win(Y, tile, ld, i, n, valid), so), buf_load<ST>(win(X, tile, ld, i, n, valid), so));
-    }
-    gossip<RPT, DEG>(cur, prev, lds, w, lane, g, eta, K);
+    for (int r = 0; r < kRpt; ++r)
+      cur[r] = fmaf(-alpha, buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so),
+                    buf_load<ST>(win(X, tile, ld, row(r), n, valid), so));
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) buf_store<ST>(win(X, tile, ld, w + kWaves * r, n, valid), so, cur[r]);
+    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-      const int i = w + kWaves * r;
-      cur[r] = buf_load<ST>(win(Y, tile, ld, i, n, valid), so) + buf_load<float>(win(Gn, tile, ld, i, n, valid), fo) -
-               buf_load<float>(win(Go, tile, ld, i, n, valid), fo);
-    }
-    gossip<RPT, DEG>(cur, prev, lds, w, lane, g, eta, K);
+    for (int r = 0; r < kRpt; ++r)
+      cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so) +
+               buf_load<float>(win(Gn, tile, ld, row(r), n, valid), fo) -
+               buf_load<float>(win(Go, tile, ld, row(r), n, valid), fo);
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) buf_store<ST>(win(Y, tile, ld, w + kWaves * r, n, valid), so, cur[r]);
+    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so, cur[r]);
   } else {
     // M(Y) first: both outputs need it
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) cur[r] = buf_load<ST>(win(Y, tile, ld, w + kWaves * r, n, valid), so);
-    gossip<RPT, DEG>(cur, prev, lds, w, lane, g, eta, K);
-    float v[RPT];
+    for (int r = 0; r < kRpt; ++r) cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so);
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+    float v[kRpt];
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) {
+    for (int r = 0; r < kRpt; ++r) {
       v[r] = cur[r];
-      cur[r] = buf_load<ST>(win(X, tile, ld, w + kWaves * r, n, valid), so);
+      cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
     }
-    gossip<RPT, DEG>(cur, prev, lds, w, lane, g, eta, K);
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-      const int i = w + kWaves * r;
-      buf_store<ST>(win(X, tile, ld, i, n, valid), so, fmaf(-alpha, v[r], cur[r]));
-      buf_store<ST>(win(Y, tile, ld, i, n, valid), so,
-                    v[r] + buf_load<float>(win(Gn, tile, ld, i, n, valid), fo) -
-                        buf_load<float>(win(Go, tile, ld, i, n, valid), fo));
+    for (int r = 0; r < kRpt; ++r) {
+      buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, fmaf(-alpha, v[r], cur[r]));
+      buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so,
+                    v[r] + buf_load<float>(win(Gn, tile, ld, row(r), n, valid), fo) -
+                        buf_load<float>(win(Go, tile, ld, row(r), n, valid), fo));
     }
   }
 }
 
-template <typename ST, int RPT, int DEG>
-int launch_k(const Shape &s, const Ell &g, int mode, void *X, void *Y, const float *Gn, const float *Go, float alpha,
-             int K, float eta, void *stream) {
+template <typename ST, int DEG, bool UNI>
+int launch_k(const Shape &s, const uint32_t *table, int mode, void *X, void *Y, const float *Gn, const float *Go,
+             float alpha, int K, float eta, void *stream) {
   const dim3 grid(ceil_div_i64(s.d, kCols));
-  const size_t lds_bytes = size_t(RPT) * kWaves * kCols * sizeof(float);  // rows padded to 4*RPT; 64 KiB at most
-  fused_generic_kernel<ST, RPT, DEG><<<grid, kThreads, lds_bytes, static_cast<hipStream_t>(stream)>>>(
-      static_cast<ST *>(X), static_cast<ST *>(Y), Gn, Go, s.n, s.d, s.ld, g, eta, alpha, K, mode);
+  const size_t lds_bytes = size_t(kRowsMax) * kCols * sizeof(float);  // 64 KiB
+  fused_generic_kernel<ST, DEG, UNI><<<grid, kThreads, lds_bytes, static_cast<hipStream_t>(stream)>>>(
+      static_cast<ST *>(X), static_cast<ST *>(Y), Gn, Go, s.n, s.d, s.ld, table, eta, alpha, K, mode);
   return hip_rc(hipGetLastError());
 }
 
-template <typename ST, int RPT>
-int launch_r(const Shape &s, const Ell &g, int deg, int mode, void *X, void *Y, const float *Gn, const float *Go,
-             float alpha, int K, float eta, void *stream) {
+template <typename ST>
+int launch_t(const Shape &s, const uint32_t *table, int deg, bool uni, int mode, void *X, void *Y, const float *Gn,
+             const float *Go, float alpha, int K, float eta, void *stream) {
+#define DETAG_CASE(DG)                                                                                   \
+  case DG:                                                                                               \
+    return uni ? launch_k<ST, DG, true>(s, table, mode, X, Y, Gn, Go, alpha, K, eta, stream)              \
+               : launch_k<ST, DG, false>(s, table, mode, X, Y, Gn, Go, alpha, K, eta, stream)
   switch (deg) {
-    case 2: return launch_k<ST, RPT, 2>(s, g, mode, X, Y, Gn, Go, alpha, K, eta, stream);
-    case 4: return launch_k<ST, RPT, 4>(s, g, mode, X, Y, Gn, Go, alpha, K, eta, stream);
-    case 8: return launch_k<ST, RPT, 8>(s, g, mode, X, Y, Gn, Go, alpha, K, eta, stream);
+    DETAG_CASE(2);
+    DETAG_CASE(4);
+    DETAG_CASE(8);
   }
+#undef DETAG_CASE
   return -1;
 }
 
-template <typename ST>
-int launch_t(const Shape &s, const Ell &g, int rpt, int deg, int mode, void *X, void *Y, const float *Gn,
-             const float *Go, float alpha, int K, float eta, void *stream) {
-  switch (rpt) {
-    case 16: return launch_r<ST, 16>(s, g, deg, mode, X, Y, Gn, Go, alpha, K, eta, stream);
-    case 32: return launch_r<ST, 32>(s, g, deg, mode, X, Y, Gn, Go, alpha, K, eta, stream);
-    case 64: return launch_r<ST, 64>(s, g, deg, mode, X, Y, Gn, Go, alpha, K, eta, stream);
-  }
-  return -1;
+uint32_t f32_bits(float f) {
+  uint32_t u;
+  static_assert(sizeof u == sizeof f, "");
+  __builtin_memcpy(&u, &f, sizeof u);
+  return u;
 }
 
 }  // namespace
 
 bool build_ell(const HostW &W, EllHost &out) {
   const int n = W.n;
-  if (n > 64 * kWaves) return false;
+  if (n > kRowsMax) return false;
   int maxdeg = 0;
+  bool uniform = true;
   for (int i = 0; i < n; ++i) {
     int cnt = 0;
-    for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k) cnt += W.colidx[k] != i;
+    float first = 0.f;
+    for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k) {
+      if (W.colidx[k] == i) continue;
+      const float v = float(W.vals[k]);
+      if (cnt == 0) first = v;
+      else if (v != first) uniform = false;
+      ++cnt;
+    }
     maxdeg = cnt > maxdeg ? cnt : maxdeg;
   }
   if (maxdeg > 8) return false;
   out.deg = maxdeg <= 2 ? 2 : maxdeg <= 4 ? 4 : 8;
-  out.rpt = n <= 16 * kWaves ? 16 : n <= 32 * kWaves ? 32 : 64;
-  const int slots = out.rpt * kWaves;
-  out.col.assign(size_t(slots) * out.deg, 0);
-  out.val.assign(size_t(slots) * out.deg, 0.f);
-  out.self.assign(slots, 0.f);
-  for (int i = 0; i < n; ++i) {
-    const int s = (i % kWaves) * out.rpt + i / kWaves;
-    int k2 = 0;
-    for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k) {
-      if (W.colidx[k] == i) {
-        out.self[s] = float(W.vals[k]);
-      } else {
-        out.col[size_t(s) * out.deg + k2] = W.colidx[k];
-        out.val[size_t(s) * out.deg + k2] = float(W.vals[k]);
-        ++k2;
+  out.uniform = uniform;
+  const int ts = table_stride(out.deg, uniform);
+  out.table.assign(size_t(kRowsMax) * ts, 0u);
+  for (int i = 0; i < kRowsMax; ++i) {
+    uint32_t *t = &out.table[size_t((i % kWaves) * kRpt + i / kWaves) * ts];
+    const uint32_t own = uint32_t(i) * kCols * 4u;  // byte offset of row i in LDS (< 65536)
+    uint32_t offs[8];
+    float vals[8];
+    for (int k = 0; k < 8; ++k) offs[k] = own, vals[k] = 0.f;  // padding: weight 0 (or a repeat, below), a valid row
+    float self = 0.f;
+    int cnt = 0;
+    if (i < n)
+      for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k) {
+        if (W.colidx[k] == i) self = float(W.vals[k]);
+        else offs[cnt] = uint32_t(W.colidx[k]) * kCols * 4u, vals[cnt] = float(W.vals[k]), ++cnt;
       }
+    for (int k = 0; k < out.deg; k += 2) t[k / 2] = offs[k] | (offs[k + 1] << 16);
+    if (uniform) {
+      // one weight for the row; a row with fewer neighbours than the table width moves the
+      // padded copies of its own value into the self weight: sum_pad w*z_i = (pad*w) z_i
+      t[out.deg / 2] = f32_bits(vals[0]);
+      self -= float(out.deg - cnt) * vals[0];
+    } else {
+      for (int k = 0; k < out.deg; ++k) t[out.deg / 2 + k] = f32_bits(vals[k]);
     }
-    for (; k2 < out.deg; ++k2) out.col[size_t(s) * out.deg + k2] = i;  // weight 0, a valid row to read
+    t[ts - 1] = f32_bits(self);
   }
   return true;
 }
@@ -215,10 +252,9 @@ bool fused_generic_available(const HostW &W, const Shape &) {
 
 int launch_fused_generic(const Shape &s, const HostW &, const DevCsr &w, int mode, void *X, void *Y, const float *Gn,
                          const float *Go, float alpha, int K, float eta, void *stream) {
-  if (K < 1 || !w.ell_col) return -1;
-  Ell g{w.ell_col, w.ell_val, w.ell_self};
-  return s.bf16 ? launch_t<bf16_t>(s, g, w.ell_rpt, w.ell_deg, mode, X, Y, Gn, Go, alpha, K, eta, stream)
-                : launch_t<float>(s, g, w.ell_rpt, w.ell_deg, mode, X, Y, Gn, Go, alpha, K, eta, stream);
+  if (K < 1 || !w.ell_table) return -1;
+  return s.bf16 ? launch_t<bf16_t>(s, w.ell_table, w.ell_deg, w.ell_uniform, mode, X, Y, Gn, Go, alpha, K, eta, stream)
+                : launch_t<float>(s, w.ell_table, w.ell_deg, w.ell_uniform, mode, X, Y, Gn, Go, alpha, K, eta, stream);
 }
 
 }  // namespace detag
