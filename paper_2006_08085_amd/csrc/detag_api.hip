@@ -24,7 +24,8 @@ struct detag_ctx {
   int ell_deg = 0;
   bool ell_uniform = false;
   bool fused_generic = false;             // build_ell succeeded for this W
-  void *scratch[2] = {nullptr, nullptr};  // per-round path: n x ld state matrices
+  // per-round path: n x ld fp32 matrices; [0],[1] hold z_r between rounds, [2],[3] the widened copies of bf16 X and Y
+  void *scratch[4] = {nullptr, nullptr, nullptr, nullptr};
   double *d_partials = nullptr;           // consensus-error partial sums
   float *d_resid = nullptr;               // gradient scratch: least-squares residuals / softmax residuals
   int64_t resid_count = 0;
@@ -47,7 +48,7 @@ detag_status hip_fail(const detag_ctx *ctx, const char *what, int rc) {
   return set_err(ctx, DETAG_EHIP, buf);
 }
 
-size_t state_bytes(const Shape &s) { return size_t(s.n) * size_t(s.ld) * (s.bf16 ? 2 : 4); }
+size_t scratch_bytes(const Shape &s) { return size_t(s.n) * size_t(s.ld) * 4; }  // fp32 whatever the state type
 
 detag_status need_device(const detag_ctx *ctx) {
   if (!ctx) return DETAG_EINVAL;
@@ -55,10 +56,10 @@ detag_status need_device(const detag_ctx *ctx) {
   return DETAG_OK;
 }
 
-detag_status need_scratch(detag_ctx *ctx, int count) {
-  for (int k = 0; k < count; ++k)
+detag_status need_scratch(detag_ctx *ctx, int first, int count) {
+  for (int k = first; k < first + count; ++k)
     if (!ctx->scratch[k]) {
-      hipError_t e = hipMalloc(&ctx->scratch[k], state_bytes(ctx->shape));
+      hipError_t e = hipMalloc(&ctx->scratch[k], scratch_bytes(ctx->shape));
       if (e != hipSuccess) {
         ctx->scratch[k] = nullptr;
         (void)hipGetLastError();
@@ -113,15 +114,17 @@ detag_status choose_path(const detag_ctx *ctx, Chosen *out) {
   return *out = kPerRound, DETAG_OK;
 }
 
-// Algorithm 3 with one launch per round.  z_r lives in the caller's buffer A or
+Shape as_f32(Shape s) { return s.bf16 = false, s; }
+
+// Algorithm 3 with one launch per round on an fp32 matrix A.  z_r lives in A or
 // in scratch; a round may write over its own z_{r-1} (each output element reads
 // only its own previous value) but never over z_r, which every neighbour reads.
-detag_status gossip_per_round(detag_ctx *ctx, void *A, int K, float eta, void *stream) {
+detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, void *stream) {
   if (K == 0) return DETAG_OK;
   const int nscratch = (K % 2 == 1 && K >= 3) ? 2 : 1;
-  if (detag_status st = need_scratch(ctx, nscratch)) return st;
+  if (detag_status st = need_scratch(ctx, 0, nscratch)) return st;
   void *B = ctx->scratch[0], *C = ctx->scratch[1];
-  const Shape &s = ctx->shape;
+  const Shape s = as_f32(ctx->shape);
   const DevCsr w = dev_csr(ctx);
   const float cm = 1.f + eta, cp = -eta;
   int rc = launch_gossip_round(s, w, A, A, B, cm, cp, stream);  // z1 -> B
@@ -146,6 +149,35 @@ detag_status gossip_per_round(detag_ctx *ctx, void *A, int K, float eta, void *s
   if (cur != A) return set_err(ctx, DETAG_EHIP, "internal: gossip result not in the caller's buffer");
   return DETAG_OK;
 }
+
+// The per-round path computes on fp32 matrices.  bf16 state is widened into
+// scratch once (exact), worked on there, and rounded once when it is written
+// back, so this path and the on-chip kernels round the same number of times.
+struct WideState {
+  detag_ctx *ctx;
+  void *user[2] = {nullptr, nullptr};
+  void *work[2] = {nullptr, nullptr};
+
+  detag_status open(void *a, void *b, void *stream) {
+    user[0] = a, user[1] = b;
+    work[0] = a, work[1] = b;
+    if (!ctx->shape.bf16) return DETAG_OK;
+    if (detag_status st = need_scratch(ctx, 2, b ? 2 : 1)) return st;
+    for (int k = 0; k < 2 && user[k]; ++k) {
+      work[k] = ctx->scratch[2 + k];
+      if (int rc = launch_widen(ctx->shape, user[k], static_cast<float *>(work[k]), stream))
+        return hip_fail(ctx, "widen", rc);
+    }
+    return DETAG_OK;
+  }
+  detag_status close(void *stream) {
+    if (!ctx->shape.bf16) return DETAG_OK;
+    for (int k = 0; k < 2 && user[k]; ++k)
+      if (int rc = launch_narrow(ctx->shape, static_cast<const float *>(work[k]), user[k], stream))
+        return hip_fail(ctx, "narrow", rc);
+    return DETAG_OK;
+  }
+};
 
 detag_status check_state_ptr(const detag_ctx *ctx, const void *p, const char *name) {
   if (!p) return set_err(ctx, DETAG_EINVAL, std::string(name) + " is NULL");
@@ -235,8 +267,7 @@ void detag_destroy(detag_ctx *ctx) {
     (void)hipFree(ctx->d_ell_table);
     (void)hipFree(ctx->d_partials);
     (void)hipFree(ctx->d_resid);
-    (void)hipFree(ctx->scratch[0]);
-    (void)hipFree(ctx->scratch[1]);
+    for (void *p : ctx->scratch) (void)hipFree(p);
   }
   delete ctx;
 }
@@ -293,8 +324,12 @@ detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double e
     case kFusedGeneric:
       rc = launch_fused_generic(ctx->shape, ctx->W, dev_csr(ctx), 0, Z_dev, nullptr, nullptr, nullptr, 0.f, K, e, stream);
       break;
-    case kPerRound:
-      return gossip_per_round(ctx, Z_dev, K, e, stream);
+    case kPerRound: {
+      WideState ws{ctx};
+      if (detag_status st = ws.open(Z_dev, nullptr, stream)) return st;
+      if (detag_status st = gossip_per_round_f32(ctx, ws.work[0], K, e, stream)) return st;
+      return ws.close(stream);
+    }
   }
   return rc ? hip_fail(ctx, "fused gossip", rc) : DETAG_OK;
 }
@@ -341,24 +376,27 @@ detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *G
     const int rc = launch_fused_generic(s, ctx->W, dev_csr(ctx), mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, K, e, stream);
     return rc ? hip_fail(ctx, "fused phase", rc) : DETAG_OK;
   }
+  WideState ws{ctx};
+  if (detag_status st = ws.open(X_dev, Y_dev, stream)) return st;
+  const Shape sf = as_f32(s);
   if (variant == DETAG_VARIANT_ATC) {
-    const int rc = launch_update_track(s, X_dev, Y_dev, Gnew_dev, Gold_dev, a, stream);
+    const int rc = launch_update_track(sf, ws.work[0], ws.work[1], Gnew_dev, Gold_dev, a, stream);
     if (rc) return hip_fail(ctx, "update", rc);
   }
-  if (detag_status st = gossip_per_round(ctx, X_dev, K, e, stream)) return st;
-  if (detag_status st = gossip_per_round(ctx, Y_dev, K, e, stream)) return st;
+  if (detag_status st = gossip_per_round_f32(ctx, ws.work[0], K, e, stream)) return st;
+  if (detag_status st = gossip_per_round_f32(ctx, ws.work[1], K, e, stream)) return st;
   if (variant == DETAG_VARIANT_ALG2) {
-    const int rc = launch_update_track(s, X_dev, Y_dev, Gnew_dev, Gold_dev, a, stream);
+    const int rc = launch_update_track(sf, ws.work[0], ws.work[1], Gnew_dev, Gold_dev, a, stream);
     if (rc) return hip_fail(ctx, "update", rc);
   }
-  return DETAG_OK;
+  return ws.close(stream);
 }
 
 detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, double alpha, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
   if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
-  if (detag_status st = need_scratch(ctx, 1)) return st;
+  if (detag_status st = need_scratch(ctx, 0, 1)) return st;
   int rc = launch_copy_state(ctx->shape, X_dev, ctx->scratch[0], stream);
   if (!rc) rc = launch_dpsgd(ctx->shape, dev_csr(ctx), ctx->scratch[0], X_dev, G_dev, float(alpha), stream);
   return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;

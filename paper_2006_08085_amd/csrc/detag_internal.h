@@ -78,6 +78,9 @@ int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const
 int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
                  void *stream);
 int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream);
+// n x ld matrices: bf16 -> fp32 (exact) and fp32 -> bf16 (round to nearest even)
+int launch_widen(const Shape &s, const void *src_bf16, float *dst, void *stream);
+int launch_narrow(const Shape &s, const float *src, void *dst_bf16, void *stream);
 
 // Fused K-round kernels.  mode: 0 = gossip only on X (Y, Gn, Go unused), 1 = ATC phase, 2 = ALG2 phase.
 // Returns -1 if no kernel exists for this (structure, n).

@@ -128,6 +128,19 @@ __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_
   }
 }
 
+// dst = src with a change of storage type (bf16 -> fp32 exact, fp32 -> bf16 round to nearest even)
+template <typename TS, typename TD, int VEC>
+__global__ __launch_bounds__(kThreads) void convert_kernel(int64_t d, int64_t ld, const TS *__restrict__ src,
+                                                           TD *__restrict__ dst) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int64_t off = int64_t(blockIdx.y) * ld + c0;
+  float x[VEC];
+  load_vec<TS, VEC>(src + off, valid, x);
+  store_vec<TD, VEC>(dst + off, valid, x);
+}
+
 // 16-byte accesses need every row start 16-byte aligned (8 bytes for bf16 vectors of four).
 bool vec_ok(const Shape &s, std::initializer_list<const void *> state_ptrs, std::initializer_list<const void *> f32_ptrs) {
   if (s.ld % 4) return false;
@@ -184,7 +197,30 @@ int launch_elementwise_t(const Shape &s, void *X, void *Y, const float *Gn, cons
   return hip_rc(hipGetLastError());
 }
 
+template <typename TS, typename TD>
+int launch_convert_t(const Shape &s, const void *src, void *dst, void *stream) {
+  const bool vec = s.ld % 4 == 0 && (reinterpret_cast<uintptr_t>(src) % (4 * sizeof(TS))) == 0 &&
+                   (reinterpret_cast<uintptr_t>(dst) % (4 * sizeof(TD))) == 0;
+  dim3 grid(ceil_div_i64(s.d, kThreads * (vec ? 4 : 1)), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    convert_kernel<TS, TD, 4><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<const TS *>(src),
+                                                         static_cast<TD *>(dst));
+  else
+    convert_kernel<TS, TD, 1><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<const TS *>(src),
+                                                         static_cast<TD *>(dst));
+  return hip_rc(hipGetLastError());
+}
+
 }  // namespace
+
+int launch_widen(const Shape &s, const void *src_bf16, float *dst, void *stream) {
+  return launch_convert_t<bf16_t, float>(s, src_bf16, dst, stream);
+}
+
+int launch_narrow(const Shape &s, const float *src, void *dst_bf16, void *stream) {
+  return launch_convert_t<float, bf16_t>(s, src, dst_bf16, stream);
+}
 
 int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float c_mix,
                         float c_prev, void *stream) {
