@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 PHASE_BYTES_PER_ELEMENT = 24   # detag_step, fp32: read X, Y, G_new, G_old; write X, Y (independent of K)
 FUSED_BYTES_PER_ELEMENT = 28   # detag_step_quadratic, fp32: read X, Y, G, b; write X, Y, G
+DPSGD_BYTES_PER_ELEMENT = 12   # detag_dpsgd_step, fp32: read X, G; write X
 
 
 def measured_traffic(fused: bool):
@@ -76,6 +77,10 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="run the step as two kernels (detag_grad_quadratic_diag, then detag_step) instead of "
                          "the single detag_step_quadratic kernel")
+    ap.add_argument("--algorithm", default="detag", choices=["detag", "dsgt", "dpsgd"],
+                    help="detag (default, the headline line); dsgt = the same kernels with K=1, eta=0; dpsgd = "
+                         "detag_grad_quadratic_diag + detag_dpsgd_step.  The two baselines of the paper's "
+                         "Experiments section, timed on the same workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of one n x ld fp32 matrix (a kernel of known "
                          "traffic, for scaling profiler byte counters); untimed")
@@ -99,6 +104,10 @@ def main():
 
     cfg = CONFIGS[args.config]
     n, d, K, alpha, sigma = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.sigma
+    alg = args.algorithm
+    eta = -1.0                      # Algorithm 3's formula from the context's lambda
+    if alg != "detag":
+        K, eta = 1, 0.0             # one plain gossip round per step
     ld = D.padded_ld(d)
     topo = D.Topology.torus(*cfg.torus_shape) if cfg.topology == "torus" else D.Topology.ring()
     ctx = D.detag_create(topo, n, d, ld)
@@ -111,20 +120,28 @@ def main():
     Ga, Gb = D.new_matrix(n, d, ld, device=dev), D.new_matrix(n, d, ld, device=dev)
 
     state = {"t": 0, "Ga": Ga, "Gb": Gb}
-    fused = not args.unfused
+    fused = not args.unfused and alg != "dpsgd"
 
     def one_step(ev=None):
-        if fused:   # gradient query + phase in one kernel; Ga is the single gradient matrix, updated in place
+        if alg == "dpsgd":
+            ctx.grad_quadratic_diag(X, h, b, state["Ga"], sigma=sigma, seed=cfg.seed, step=state["t"])
             if ev is not None:
                 ev[0].record()
-            ctx.step_quadratic(X, Y, state["Ga"], h, b, alpha, K, sigma=sigma, seed=cfg.seed, step=state["t"])
+            ctx.dpsgd_step(X, state["Ga"], alpha)
+            if ev is not None:
+                ev[1].record()
+        elif fused:   # gradient query + phase in one kernel; Ga is the single gradient matrix, updated in place
+            if ev is not None:
+                ev[0].record()
+            ctx.step_quadratic(X, Y, state["Ga"], h, b, alpha, K, sigma=sigma, seed=cfg.seed, step=state["t"],
+                               eta=eta)
             if ev is not None:
                 ev[1].record()
         else:
             ctx.grad_quadratic_diag(X, h, b, state["Ga"], sigma=sigma, seed=cfg.seed, step=state["t"])
             if ev is not None:
                 ev[0].record()
-            ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K)
+            ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K, eta)
             if ev is not None:
                 ev[1].record()
             state["Ga"], state["Gb"] = state["Gb"], state["Ga"]
@@ -149,7 +166,7 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     phase_ms = sum(a.elapsed_time(b_) for a, b_ in evs) / args.steps
-    bpe = FUSED_BYTES_PER_ELEMENT if fused else PHASE_BYTES_PER_ELEMENT
+    bpe = DPSGD_BYTES_PER_ELEMENT if alg == "dpsgd" else FUSED_BYTES_PER_ELEMENT if fused else PHASE_BYTES_PER_ELEMENT
     achieved = bpe * n * d / (phase_ms * 1e-3) / 1e9
     xbar = ctx.mean(X)
     finite = bool(torch.isfinite(xbar[:d]).all().item())
@@ -165,17 +182,20 @@ def main():
                                f"{'8x8 torus' if cfg.topology == 'torus' else 'ring'}, d={d} fp32 (ld={ld}), "
                                f"K={K} accelerated-gossip rounds of X and Y per step, diagonal quadratic + "
                                f"N(0,{sigma}^2) counter-based noise, lr={alpha}",
-                   "step": "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
+                   "algorithm": alg,
+                   "step": "detag_grad_quadratic_diag + detag_dpsgd_step" if alg == "dpsgd"
+                           else "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
                            else "detag_grad_quadratic_diag + detag_step (ATC, fused K rounds)",
                    "finite": finite},
         "roofline": {"bound": "hbm",
-                     "kernel": "fused_quadratic_kernel (detag_step_quadratic)" if fused
+                     "kernel": "fused_structured_kernel, D-PSGD mode (detag_dpsgd_step)" if alg == "dpsgd"
+                               else "fused_quadratic_kernel (detag_step_quadratic)" if fused
                                else "fused_structured_kernel (detag_step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(fused) if args.config == 4 else None, "kernel_ms": phase_ms,
+                     "traffic": measured_traffic(fused) if args.config == 4 and alg == "detag" else None, "kernel_ms": phase_ms,
                      "algorithmic_bytes_per_launch": bpe * n * d},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and alg == "detag":
         out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample_cols, d))
     print(json.dumps(out))
 

@@ -396,6 +396,13 @@ detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, d
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
   if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (!std::isfinite(alpha)) return set_err(ctx, DETAG_EINVAL, "alpha must be finite");
+  if (static_cast<const void *>(G_dev) == X_dev) return set_err(ctx, DETAG_EINVAL, "X and G must not overlap");
+  if (ctx->path != DETAG_PATH_PER_ROUND && fused_structured_available(ctx->W)) {  // one pass, 12 B per element
+    const int rc = launch_fused_structured(ctx->shape, ctx->W, 3, X_dev, nullptr, G_dev, nullptr, float(alpha), 1, 0.f,
+                                           stream);
+    return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
+  }
   if (detag_status st = need_scratch(ctx, 0, 1)) return st;
   int rc = launch_copy_state(ctx->shape, X_dev, ctx->scratch[0], stream);
   if (!rc) rc = launch_dpsgd(ctx->shape, dev_csr(ctx), ctx->scratch[0], X_dev, G_dev, float(alpha), stream);

@@ -72,7 +72,7 @@ __device__ __forceinline__ void ag_rounds(float (&u)[T::n], float (&p)[T::n], co
 // floats per lane, plus the loads in flight.  The kernel asks for the matching
 // waves-per-SIMD so the register allocator works against the real budget.
 constexpr int waves_per_simd(int n, int mode) {
-  const int need = n * (mode == 0 ? 2 : 3) + 40;
+  const int need = n * (mode == 0 || mode == 3 ? 2 : 3) + 40;
   const int w = 512 / need;
   return w < 1 ? 1 : w > 8 ? 8 : w;
 }

@@ -25,6 +25,7 @@ using namespace fused;
 
 // MODE 0: Z <- M(Z) on X.  MODE 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
 // MODE 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
+// MODE 3 (D-PSGD baseline of the Experiments section): X <- W^T X - alpha*Gn, one plain round (c built with eta = 0).
 template <class T, typename ST, int MODE>
 __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_structured_kernel(
     ST *X, ST *Y, const float *__restrict__ Gn, const float *__restrict__ Go, int64_t d, int64_t ld, Coef c,
@@ -45,7 +46,24 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_st
     X = launder_uniform(X);
 #pragma unroll
     for (int i = 0; i < N; ++i) buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+  } else if constexpr (MODE == 3) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) u[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
+    __builtin_amdgcn_sched_barrier(0);
+    X = launder_uniform(X);
+    float lg[N];  // gradient rows arrive a few rows ahead of the stores that consume them
+#pragma unroll
+    for (int i = 0; i < D; ++i) lg[i] = buf_load<float>(row_of(Gn, tile, ld, i, valid), go4);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      if (i + D < N) lg[i + D] = buf_load<float>(row_of(Gn, tile, ld, i + D, valid), go4);
+      const float mixed = fmaf(c.b, nb_sum<T>(u, i), c.a_first * u[i]);
+      buf_store<ST>(row_of(X, tile, ld, i, valid), so, fmaf(-alpha, lg[i], mixed));
+      __builtin_amdgcn_sched_barrier(0);
+    }
   } else {
+    static_assert(MODE == 1 || MODE == 2, "unknown mode");
     float v[N];
     if constexpr (MODE == 1) {
       float lx[N], ly[N], lgn[N], lgo[N];
@@ -124,6 +142,7 @@ int launch_t(const Shape &s, int mode, void *X, void *Y, const float *Gn, const 
   switch (mode) {
     case 0: fused_structured_kernel<T, ST, 0><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
     case 1: fused_structured_kernel<T, ST, 1><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
+    case 3: fused_structured_kernel<T, ST, 3><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
     default: fused_structured_kernel<T, ST, 2><<<grid, kThreads, 0, st>>>(x, y, Gn, Go, s.d, s.ld, c, alpha, K); break;
   }
   return hip_rc(hipGetLastError());
