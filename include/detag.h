@@ -126,6 +126,15 @@ void detag_destroy(detag_ctx *ctx);
 detag_status detag_get_spectrum(const detag_ctx *ctx, double *lambda2, double *lambdan,
                                 double *lambda, double *eta);
 
+/*
+ * Phase length suggested by Theorem 3 for the context's W:
+ *   R = max(log(n)/2, log(outer_ratio)/2) / sqrt(1 - lambda), rounded up, at least 1,
+ * with outer_ratio = varsigma_0^2 T / (Delta L) in the theorem's notation; pass a
+ * value <= 0 to leave that term out (R then depends on n and lambda only).
+ * DETAG_EINVAL if W has no stored lambda (asymmetric W) or R does not fit an int32.
+ */
+detag_status detag_get_phase_length(const detag_ctx *ctx, double outer_ratio, int32_t *R);
+
 /* Host views of W as stored (row i = pairs (j, W_ji), self included, j ascending).
  * The arrays belong to the context and live until detag_destroy. */
 detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const int32_t **rowptr,

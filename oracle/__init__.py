@@ -12,7 +12,7 @@ Not pinned (no data in the paper to pin to): the training-loss curves of the
 "Experiments" section — parity unpinned for those; they are not reproduced.
 """
 from .topology import (mixing_matrix, slack, spectrum, eta_from_lambda,  # noqa: F401
-                       neighbour_lists, check_gossip_matrix)
+                       neighbour_lists, check_gossip_matrix, phase_length)
 from .gossip import (accelerated_gossip, tracking_update, detag_step,  # noqa: F401
                      worker_mean, consensus_error, dpsgd_step)
 from .objectives import (grad_lstsq, grad_quadratic_diag, grad_softmax,  # noqa: F401

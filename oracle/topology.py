@@ -94,6 +94,15 @@ def eta_from_lambda(lam: float) -> float:
     return float((1.0 - s) / (1.0 + s))
 
 
+def phase_length(lam: float, n: int, outer_ratio: float = 0.0) -> int:
+    """Phase length suggested by Theorem 3: R = max(log(n)/2, log(r)/2) / sqrt(1 - lambda), with
+    r = varsigma_0^2 T / (Delta L) (pass 0 to leave that term out), rounded up and at least 1."""
+    lead = 0.5 * np.log(n)
+    if outer_ratio > 0.0:
+        lead = max(lead, 0.5 * np.log(outer_ratio))
+    return max(1, int(np.ceil(lead / np.sqrt(1.0 - lam))))
+
+
 def neighbour_lists(W: np.ndarray):
     """For every worker i the list of (j, W[j, i]) with W[j, i] != 0, self
     included — the terms of the sum in the gossip equation, which reads

@@ -30,7 +30,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
                  "DETAG_EUNSUPPORTED", "DETAG_ENOMEM", "DETAG_EHIP"]
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
-           "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step",
+           "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step",
            "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
     L.detag_destroy.restype = None
     L.detag_get_spectrum.argtypes = [vp] + [C.POINTER(f64)] * 4
     L.detag_get_spectrum.restype = C.c_int
+    L.detag_get_phase_length.argtypes = [vp, f64, C.POINTER(i32)]
+    L.detag_get_phase_length.restype = C.c_int
     L.detag_get_csr.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(C.POINTER(i32)),
                                 C.POINTER(C.POINTER(i32)), C.POINTER(C.POINTER(f64))]
     L.detag_get_csr.restype = C.c_int
@@ -219,6 +221,11 @@ class Context:
         self._check(lib().detag_get_spectrum(self._h, *[C.byref(x) for x in v]))
         return dict(lambda2=v[0].value, lambdan=v[1].value, lam=v[2].value, eta=v[3].value)
 
+    def phase_length(self, outer_ratio: float = 0.0) -> int:
+        R = C.c_int32()
+        self._check(lib().detag_get_phase_length(self._h, outer_ratio, C.byref(R)))
+        return R.value
+
     def csr(self):
         n, nnz = C.c_int32(), C.c_int64()
         rp, ci, va = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)(), C.POINTER(C.c_double)()
@@ -354,6 +361,7 @@ def detag_create(topology: Topology, n: int, d: int, ld: Optional[int] = None, d
 def detag_destroy(ctx: Context): ctx.close()
 def detag_get_spectrum(ctx: Context): return ctx.spectrum()
 def detag_get_csr(ctx: Context): return ctx.csr()
+def detag_get_phase_length(ctx: Context, outer_ratio=0.0): return ctx.phase_length(outer_ratio)
 def detag_set_path(ctx: Context, path: int): ctx.set_path(path)
 def detag_has_fused(ctx: Context): return ctx.has_fused()
 def detag_gossip_accel(ctx: Context, Z, K, eta=-1.0): ctx.gossip_accel(Z, K, eta)

@@ -3,6 +3,7 @@
 // method happens on the host after detag_create.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -126,8 +127,7 @@ detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, voi
   void *B = ctx->scratch[0], *C = ctx->scratch[1];
   const Shape s = as_f32(ctx->shape);
   const DevCsr w = dev_csr(ctx);
-  const float cm = 1.f + eta, cp = -eta;
-  int rc = launch_gossip_round(s, w, A, A, B, cm, cp, stream);  // z1 -> B
+  int rc = launch_gossip_round(s, w, A, A, B, eta, stream);  // z1 -> B
   if (rc) return hip_fail(ctx, "gossip round", rc);
   if (K == 1) {
     rc = launch_copy_state(s, B, A, stream);
@@ -136,13 +136,13 @@ detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, voi
   int r = 1;           // next round computes z_{r+1}
   void *cur = B, *prev = A;
   if (K % 2 == 1) {    // shift parity once through the third buffer: z2 -> C, z3 -> A
-    rc = launch_gossip_round(s, w, B, A, C, cm, cp, stream);
-    if (!rc) rc = launch_gossip_round(s, w, C, B, A, cm, cp, stream);
+    rc = launch_gossip_round(s, w, B, A, C, eta, stream);
+    if (!rc) rc = launch_gossip_round(s, w, C, B, A, eta, stream);
     if (rc) return hip_fail(ctx, "gossip round", rc);
     r = 3, cur = A, prev = C;
   }
   for (; r < K; ++r) {  // z_{r+1} overwrites z_{r-1}
-    rc = launch_gossip_round(s, w, cur, prev, prev, cm, cp, stream);
+    rc = launch_gossip_round(s, w, cur, prev, prev, eta, stream);
     if (rc) return hip_fail(ctx, "gossip round", rc);
     void *t = cur; cur = prev; prev = t;
   }
@@ -278,6 +278,20 @@ detag_status detag_get_spectrum(const detag_ctx *ctx, double *lambda2, double *l
   if (lambdan) *lambdan = ctx->W.lambdan;
   if (lambda) *lambda = ctx->W.lambda;
   if (eta) *eta = ctx->W.eta;
+  return DETAG_OK;
+}
+
+detag_status detag_get_phase_length(const detag_ctx *ctx, double outer_ratio, int32_t *R) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (!R) return set_err(ctx, DETAG_EINVAL, "R is NULL");
+  const double lam = ctx->W.lambda;
+  if (std::isnan(lam)) return set_err(ctx, DETAG_EINVAL, "W is not symmetric, so it has no stored lambda");
+  if (std::isnan(outer_ratio)) return set_err(ctx, DETAG_EINVAL, "outer_ratio is NaN");
+  double lead = 0.5 * std::log(double(ctx->W.n));
+  if (outer_ratio > 0.0) lead = std::max(lead, 0.5 * std::log(outer_ratio));
+  const double r = std::ceil(lead / std::sqrt(1.0 - lam));
+  if (!(r < 2147483647.0)) return set_err(ctx, DETAG_EINVAL, "phase length does not fit an int32");
+  *R = r < 1.0 ? 1 : int32_t(r);
   return DETAG_OK;
 }
 

@@ -66,9 +66,9 @@ struct Shape {
   bool bf16;  // storage of X/Y
 };
 
-// One gossip round, out = c_mix * (W^T cur) + c_prev * prev.  out may alias prev; out != cur.
-int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out,
-                        float c_mix, float c_prev, void *stream);
+// One round of Algorithm 3, out = (1+eta) * (W^T cur) - eta * prev.  out may alias prev; out != cur.
+int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float eta,
+                        void *stream);
 // Y += Gnew - Gold
 int launch_track(const Shape &s, void *Y, const float *Gn, const float *Go, void *stream);
 // X -= alpha*Y (old Y); Y += Gnew - Gold   (one pass)

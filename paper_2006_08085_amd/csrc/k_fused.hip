@@ -58,8 +58,7 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_st
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       if (i + D < N) lg[i + D] = buf_load<float>(row_of(Gn, tile, ld, i + D, valid), go4);
-      const float mixed = fmaf(c.b, nb_sum<T>(u, i), c.a_first * u[i]);
-      buf_store<ST>(row_of(X, tile, ld, i, valid), so, fmaf(-alpha, lg[i], mixed));
+      buf_store<ST>(row_of(X, tile, ld, i, valid), so, fmaf(-alpha, lg[i], fmaf(c.b, lap<T>(u, i), u[i])));
       __builtin_amdgcn_sched_barrier(0);
     }
   } else {

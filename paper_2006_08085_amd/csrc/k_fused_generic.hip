@@ -26,67 +26,68 @@ namespace {
 constexpr int kWaves = 16, kThreads = 64 * kWaves, kCols = 64, kRpt = 16, kRowsMax = kWaves * kRpt;  // 256 rows
 
 // Table words per row: DEG/2 words of packed 16-bit LDS byte offsets, then the
-// neighbour weights (one word if they are all equal, else DEG), then W_ii.
-constexpr int table_stride(int deg, bool uniform) { return deg / 2 + (uniform ? 1 : deg) + 1; }
+// neighbour weights (one word if they are all equal, else DEG).  W_ii is not
+// stored: a round is evaluated in velocity form, v = z_r - z_{r-1},
+//   v_i <- (1+eta) * sum_j W_ji (z_j - z_i) + eta * v_i,   z_i <- z_i + v_i,
+// in which equal values across the workers are a fixed point exactly whatever
+// the rounding of the weights (the worker mean does not drift with K) and the
+// only rounding at the magnitude of z is the last add.
+// Padding entries point at the row itself (difference zero).
+constexpr int table_stride(int deg, bool uniform) { return deg / 2 + (uniform ? 1 : deg); }
 
 template <int DEG, bool UNI>
 struct RowTab {
   uint32_t w[table_stride(DEG, UNI)];
   __device__ __forceinline__ uint32_t off(int k) const { return (k & 1) ? w[k >> 1] >> 16 : w[k >> 1] & 0xffffu; }
   __device__ __forceinline__ float val(int k) const { return __uint_as_float(w[DEG / 2 + (UNI ? 0 : k)]); }
-  __device__ __forceinline__ float self() const { return __uint_as_float(w[table_stride(DEG, UNI) - 1]); }
 };
 
-// p <- (1+eta) * (W_ii*z_own + sum_k W_ji * lds[j]) - eta * p, for this lane's rows; then publish p.
-template <int DEG, bool UNI>
-__device__ __forceinline__ void round_step(const float (&z)[kRpt], float (&p)[kRpt], const char *lds_b, float *lds,
-                                           int w, int lane, const RowTab<DEG, UNI> (&tab)[kRpt], float cm,
-                                           float neg_eta) {
+// One round for this lane's rows: v <- cm * sum_k W_ji (lds[j] - z) + eta * v;  z <- z + v;  then publish z.
+template <int DEG, bool UNI, bool FIRST>
+__device__ __forceinline__ void round_step(float (&z)[kRpt], float (&v)[kRpt], const char *lds_b, float *lds, int w,
+                                           int lane, const RowTab<DEG, UNI> (&tab)[kRpt], float cm, float eta) {
   const uint32_t lane4 = uint32_t(lane) * 4u;
+  auto nb = [&](int r, int k) { return *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4)); };
 #pragma unroll
   for (int r = 0; r < kRpt; ++r) {
     float acc;
     if constexpr (UNI) {
-      float s = *reinterpret_cast<const float *>(lds_b + (tab[r].off(0) + lane4));
+      // pairwise tree: DEG equal values sum exactly, so s - DEG*z is exactly zero for them
+      float s[DEG];
 #pragma unroll
-      for (int k = 1; k < DEG; ++k) s += *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4));
-      acc = fmaf(tab[r].val(0), s, tab[r].self() * z[r]);
+      for (int k = 0; k < DEG; ++k) s[k] = nb(r, k);
+#pragma unroll
+      for (int len = DEG / 2; len >= 1; len /= 2)
+#pragma unroll
+        for (int k = 0; k < len; ++k) s[k] += s[k + len];
+      acc = tab[r].val(0) * fmaf(-float(DEG), z[r], s[0]);
     } else {
-      acc = tab[r].self() * z[r];
+      acc = 0.f;
 #pragma unroll
-      for (int k = 0; k < DEG; ++k)
-        acc = fmaf(tab[r].val(k), *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4)), acc);
+      for (int k = 0; k < DEG; ++k) acc = fmaf(tab[r].val(k), nb(r, k) - z[r], acc);
     }
-    p[r] = fmaf(cm, acc, neg_eta * p[r]);
+    v[r] = FIRST ? cm * acc : fmaf(cm, acc, eta * v[r]);
   }
   __syncthreads();  // every read of z_r is done
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r) lds[(w + kWaves * r) * kCols + lane] = p[r];
+  for (int r = 0; r < kRpt; ++r) {
+    z[r] += v[r];
+    lds[(w + kWaves * r) * kCols + lane] = z[r];
+  }
   __syncthreads();  // z_{r+1} is visible
 }
 
-// K >= 1 rounds from z_{-1} = z_0 = cur.  Result in cur; prev is scratch.
+// K >= 1 rounds from z_{-1} = z_0 = z.  Result in z; v is scratch.
 template <int DEG, bool UNI>
-__device__ __forceinline__ void gossip(float (&cur)[kRpt], float (&prev)[kRpt], float *lds, int w, int lane,
+__device__ __forceinline__ void gossip(float (&z)[kRpt], float (&v)[kRpt], float *lds, int w, int lane,
                                        const RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
-  const float cm = 1.f + eta, neg_eta = -eta;
+  const float cm = 1.f + eta;
   const char *lds_b = reinterpret_cast<const char *>(lds);
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r) {
-    lds[(w + kWaves * r) * kCols + lane] = cur[r];
-    prev[r] = cur[r];
-  }
+  for (int r = 0; r < kRpt; ++r) lds[(w + kWaves * r) * kCols + lane] = z[r];
   __syncthreads();
-  int r = 0;
-  for (; r + 2 <= K; r += 2) {
-    round_step<DEG, UNI>(cur, prev, lds_b, lds, w, lane, tab, cm, neg_eta);
-    round_step<DEG, UNI>(prev, cur, lds_b, lds, w, lane, tab, cm, neg_eta);
-  }
-  if (r < K) {
-    round_step<DEG, UNI>(cur, prev, lds_b, lds, w, lane, tab, cm, neg_eta);
-#pragma unroll
-    for (int q = 0; q < kRpt; ++q) cur[q] = prev[q];
-  }
+  round_step<DEG, UNI, true>(z, v, lds_b, lds, w, lane, tab, cm, eta);
+  for (int r = 1; r < K; ++r) round_step<DEG, UNI, false>(z, v, lds_b, lds, w, lane, tab, cm, eta);
 }
 
 // Window of row i of the tile; rows >= n get an empty window (loads give 0, stores are dropped).
@@ -224,23 +225,14 @@ bool build_ell(const HostW &W, EllHost &out) {
     uint32_t offs[8];
     float vals[8];
     for (int k = 0; k < 8; ++k) offs[k] = own, vals[k] = 0.f;  // padding: weight 0 (or a repeat, below), a valid row
-    float self = 0.f;
     int cnt = 0;
     if (i < n)
-      for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k) {
-        if (W.colidx[k] == i) self = float(W.vals[k]);
-        else offs[cnt] = uint32_t(W.colidx[k]) * kCols * 4u, vals[cnt] = float(W.vals[k]), ++cnt;
-      }
+      for (int k = W.rowptr[i]; k < W.rowptr[i + 1]; ++k)
+        if (W.colidx[k] != i) offs[cnt] = uint32_t(W.colidx[k]) * kCols * 4u, vals[cnt] = float(W.vals[k]), ++cnt;
     for (int k = 0; k < out.deg; k += 2) t[k / 2] = offs[k] | (offs[k + 1] << 16);
-    if (uniform) {
-      // one weight for the row; a row with fewer neighbours than the table width moves the
-      // padded copies of its own value into the self weight: sum_pad w*z_i = (pad*w) z_i
-      t[out.deg / 2] = f32_bits(vals[0]);
-      self -= float(out.deg - cnt) * vals[0];
-    } else {
+    if (uniform) t[out.deg / 2] = f32_bits(vals[0]);  // one weight for the row; padded entries repeat the row itself
+    else
       for (int k = 0; k < out.deg; ++k) t[out.deg / 2 + k] = f32_bits(vals[k]);
-    }
-    t[ts - 1] = f32_bits(self);
   }
   return true;
 }

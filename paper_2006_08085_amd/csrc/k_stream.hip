@@ -54,8 +54,13 @@ __device__ __forceinline__ void store_vec(ST *p, int valid, const float (&v)[VEC
     if (e < valid) p[e] = from_f32<ST>(v[e]);
 }
 
-// out[i,:] = c_mix * sum_k w[k] * cur[col[k],:] + c_prev * prev[i,:]  for rows i in this block's group.
-// With HAS_G: out[i,:] -= alpha * G[i,:] (D-PSGD) and prev is not read.
+// One round in difference form, for the rows i of this block's group:
+//   out[i,:] = cur[i,:] + c_mix * sum_k w[k] * (cur[col[k],:] - cur[i,:]) + eta * (cur[i,:] - prev[i,:])
+// (= c_mix * (W^T cur)[i,:] - eta * prev[i,:] for c_mix = 1 + eta, the rows of W^T summing to one).  Written
+// this way, equal values across the workers are reproduced exactly whatever the rounding of the weights, so
+// the worker mean does not drift over many rounds; and the increment is formed at its own (small) magnitude,
+// so the only rounding at the magnitude of the state is the last add.
+// With HAS_G: out[i,:] = cur[i,:] + sum_k ... - alpha * G[i,:] (D-PSGD) and prev is not read.
 template <typename ST, int VEC, bool HAS_G>
 __global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d, int64_t ld,
                                                                 const int32_t *__restrict__ rowptr,
@@ -63,35 +68,38 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d
                                                                 const float *__restrict__ vals,
                                                                 const ST *__restrict__ cur, const ST *prev, ST *out,
                                                                 const float *__restrict__ G, float c_mix,
-                                                                float c_prev, float alpha, int rows_per_group) {
+                                                                float eta, float alpha, int rows_per_group) {
   const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
   if (c0 >= d) return;
   const int valid = int(d - c0 < VEC ? d - c0 : VEC);
   const int r0 = blockIdx.y * rows_per_group;
   const int r1 = r0 + rows_per_group < n ? r0 + rows_per_group : n;
   for (int i = r0; i < r1; ++i) {
-    float acc[VEC];
+    float own[VEC], acc[VEC];
+    load_vec<ST, VEC>(cur + int64_t(i) * ld + c0, valid, own);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
     const int k1 = rowptr[i + 1];
     for (int k = rowptr[i]; k < k1; ++k) {
+      const int j = colidx[k];
+      if (j == i) continue;  // the diagonal entry contributes a zero difference
       const float w = vals[k];
       float v[VEC];
-      load_vec<ST, VEC>(cur + int64_t(colidx[k]) * ld + c0, valid, v);
+      load_vec<ST, VEC>(cur + int64_t(j) * ld + c0, valid, v);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(w, v[e], acc[e]);
+      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(w, v[e] - own[e], acc[e]);
     }
     float o[VEC];
     if constexpr (HAS_G) {
       float g[VEC];
       load_vec<float, VEC>(G + int64_t(i) * ld + c0, valid, g);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) o[e] = fmaf(-alpha, g[e], c_mix * acc[e]);
+      for (int e = 0; e < VEC; ++e) o[e] = own[e] + fmaf(-alpha, g[e], c_mix * acc[e]);
     } else {
       float p[VEC];
       load_vec<ST, VEC>(prev + int64_t(i) * ld + c0, valid, p);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) o[e] = fmaf(c_mix, acc[e], c_prev * p[e]);
+      for (int e = 0; e < VEC; ++e) o[e] = own[e] + fmaf(c_mix, acc[e], eta * (own[e] - p[e]));
     }
     store_vec<ST, VEC>(out + int64_t(i) * ld + c0, valid, o);
   }
@@ -163,7 +171,7 @@ int rows_per_group_for(const Shape &s, int col_blocks) {
 
 template <typename ST, bool HAS_G>
 int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, const float *G,
-                   float c_mix, float c_prev, float alpha, void *stream) {
+                   float c_mix, float eta, float alpha, void *stream) {
   const bool vec = vec_ok(s, {cur, prev, out}, {G});
   const int per_block = kThreads * (vec ? 4 : 1);
   const int col_blocks = ceil_div_i64(s.d, per_block);
@@ -173,11 +181,11 @@ int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void 
   if (vec)
     gossip_round_kernel<ST, 4, HAS_G><<<grid, kThreads, 0, st>>>(
         s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
-        static_cast<ST *>(out), G, c_mix, c_prev, alpha, rpg);
+        static_cast<ST *>(out), G, c_mix, eta, alpha, rpg);
   else
     gossip_round_kernel<ST, 1, HAS_G><<<grid, kThreads, 0, st>>>(
         s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
-        static_cast<ST *>(out), G, c_mix, c_prev, alpha, rpg);
+        static_cast<ST *>(out), G, c_mix, eta, alpha, rpg);
   return hip_rc(hipGetLastError());
 }
 
@@ -222,10 +230,10 @@ int launch_narrow(const Shape &s, const float *src, void *dst_bf16, void *stream
   return launch_convert_t<float, bf16_t>(s, src, dst_bf16, stream);
 }
 
-int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float c_mix,
-                        float c_prev, void *stream) {
-  return s.bf16 ? launch_round_t<bf16_t, false>(s, w, cur, prev, out, nullptr, c_mix, c_prev, 0.f, stream)
-                : launch_round_t<float, false>(s, w, cur, prev, out, nullptr, c_mix, c_prev, 0.f, stream);
+int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float eta,
+                        void *stream) {
+  return s.bf16 ? launch_round_t<bf16_t, false>(s, w, cur, prev, out, nullptr, 1.f + eta, eta, 0.f, stream)
+                : launch_round_t<float, false>(s, w, cur, prev, out, nullptr, 1.f + eta, eta, 0.f, stream);
 }
 
 int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,

@@ -20,8 +20,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     if (r) k0 += W0, k1 += W1;
-    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint64_t p0 = uint64_t(M0) * c0, p1 = uint64_t(M1) * c2;  // one 32x32->64 multiply each
+    const uint32_t hi0 = uint32_t(p0 >> 32), lo0 = uint32_t(p0);
+    const uint32_t hi1 = uint32_t(p1 >> 32), lo1 = uint32_t(p1);
     c0 = hi1 ^ c1 ^ k0;
     c1 = lo1;
     c2 = hi0 ^ c3 ^ k1;
@@ -32,12 +33,15 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 __device__ __forceinline__ float unit_open(uint32_t r) { return (float(r >> 9) + 0.5f) * 0x1p-23f; }
 
+// The hardware's log2, sqrt and sin/cos (the last two take their argument in revolutions, which is what the
+// transform needs) are used directly: over all 2^23 values u can take, sin and cos are within 1.3e-7
+// (absolute) and the radius within 1.4e-7 (relative) of the exact values.
 __device__ __forceinline__ void box_muller(uint32_t ra, uint32_t rb, float &z0, float &z1) {
-  const float rad = sqrtf(-2.0f * logf(unit_open(ra)));
-  float s, c;
-  sincospif(2.0f * unit_open(rb), &s, &c);
-  z0 = rad * c;
-  z1 = rad * s;
+  constexpr float kTwoLn2 = 1.3862943611198906f;  // -2 ln u = -(2 ln 2) log2 u
+  const float rad = __builtin_amdgcn_sqrtf(-kTwoLn2 * __builtin_amdgcn_logf(unit_open(ra)));
+  const float rev = unit_open(rb);
+  z0 = rad * __builtin_amdgcn_cosf(rev);
+  z1 = rad * __builtin_amdgcn_sinf(rev);
 }
 
 // The four standard normals of one Philox block.

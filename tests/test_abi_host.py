@@ -106,6 +106,22 @@ def test_linear_graph_lambda_through_csr():
     assert np.array_equal(ctx.dense_W(), W)
 
 
+def test_phase_length_of_theorem_3():
+    """Host-side formula: same integer as the oracle's, the outer-variance term takes over when it is the
+    larger one, and an asymmetric W (no stored lambda) is an error, not a guess."""
+    for kappa in (1.0, 0.1, 0.05, 0.01):
+        ctx = D.detag_create(D.Topology.ring(kappa=kappa), 16, 8)
+        lam = ctx.spectrum()["lam"]
+        assert ctx.phase_length() == T.phase_length(lam, 16)
+        assert ctx.phase_length(1e6) == T.phase_length(lam, 16, 1e6) > ctx.phase_length()
+        assert ctx.phase_length(2.0) == ctx.phase_length()          # log(2)/2 < log(16)/2
+    assert D.detag_create(D.Topology.ring(), 1, 8).phase_length() == 1
+    P = np.roll(np.eye(5), 1, axis=1)
+    with pytest.raises(D.DetagError) as ei:
+        D.detag_create(D.Topology.from_dense(0.5 * np.eye(5) + 0.5 * P), 5, 4).phase_length()
+    assert ei.value.status == D.DETAG_EINVAL
+
+
 def test_asymmetric_W_is_accepted_without_eta():
     P = np.roll(np.eye(5), 1, axis=1)
     W = 0.5 * np.eye(5) + 0.5 * P

@@ -94,3 +94,45 @@ def test_first_workload_ordering_of_the_three_algorithms():
     assert ce["dsgt"] < 1e-2 * ce["dpsgd"]
     loss = lambda x: 0.5 * np.mean([np.sum((A[i].astype(np.float64) @ x - b[i]) ** 2) for i in range(n)])
     assert loss(out["detag"][0].mean(0)) < loss(out["dpsgd"][0].mean(0))
+
+
+def _golden_hyper(golden_dir):
+    import os
+    rows = [ln.split() for ln in open(os.path.join(golden_dir, "paper_detag_hyperparameters.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    return {float(k): (float(e), int(r)) for k, e, r in rows}
+
+
+def test_spectral_gap_sweep_on_the_quadratic(golden_dir):
+    """Second experiment of the paper on the synthetic quadratic: ring-16, W_kappa, lr 0.5.  With Algorithm 3's
+    eta and Theorem 3's phase length DeTAG holds its consensus distance (within a small factor) at every kappa (the number of
+    rounds per phase grows as 1/sqrt(gap)); DSGT and D-PSGD get worse as the gap closes; DeTAG with the
+    (eta, R) pairs the paper tuned sits between; at kappa = 1 that pair is (0, 1), i.e. DSGT itself."""
+    from oracle import noise as ON
+    from workloads import CONFIGS
+    cfg = CONFIGS[2]
+    n, d, T_steps = cfg.n, 600, 40
+    h, b = gen.quadratic_problem(n, d, seed=cfg.seed, b_mean="i/n")
+    noise = [ON.normal_noise(cfg.seed, t, n, np.arange(d)) for t in range(T_steps)]
+    grad = lambda t, X: O.grad_quadratic_diag(X, h, b, noise[t], cfg.sigma)
+    W0 = T.mixing_matrix(n, gen.edges_ring(n))
+    tuned = _golden_hyper(golden_dir)
+    ce = {}
+    for kappa in (1.0, 0.1, 0.05, 0.01):
+        W = T.slack(W0, kappa)
+        lam = T.spectrum(W)[2]
+        settings = {"dpsgd": ("dpsgd", 1, 0.0), "dsgt": ("dsgt", 1, 0.0),
+                    "tuned": ("detag", tuned[kappa][1], tuned[kappa][0]),
+                    "theory": ("detag", T.phase_length(lam, n), T.eta_from_lambda(lam))}
+        for name, (alg, K, eta) in settings.items():
+            X, _, _ = R.run(alg, grad, np.zeros((n, d)), W, cfg.lr, T_steps, K=K, eta=eta)
+            ce[kappa, name] = G.consensus_error(X)
+        assert ce[kappa, "theory"] < 1e-2 * ce[kappa, "dsgt"]
+        assert ce[kappa, "tuned"] <= ce[kappa, "dsgt"] < ce[kappa, "dpsgd"]
+    assert ce[1.0, "tuned"] == ce[1.0, "dsgt"]
+    theory = [ce[k, "theory"] for k in (1.0, 0.1, 0.05, 0.01)]
+    assert max(theory) < 5 * min(theory)                      # flat to a small factor, against > 20x for DSGT
+    for name in ("dsgt", "dpsgd"):
+        seq = [ce[k, name] for k in (1.0, 0.1, 0.05, 0.01)]
+        assert all(a < b_ for a, b_ in zip(seq, seq[1:]))
+    assert ce[0.01, "dsgt"] > 20 * ce[1.0, "dsgt"]

@@ -92,6 +92,25 @@ def test_printed_ring16_gaps(golden_dir):
     assert float(f"{third:.0e}") == pytest.approx(5e-2)
 
 
+def test_phase_length_meets_the_condition_the_proof_needs():
+    """The proof of Theorem 3 needs R >= log(n) / (2 sqrt(1-lambda)), which it shows is enough for
+    (1 - sqrt(1-lambda))^R <= n^(-1/2); the suggested R must satisfy both, be minimal for the first, and
+    scale as 1/sqrt(gap) under the slack construction (gap -> kappa*gap)."""
+    for n in (8, 16, 64, 256):
+        for lam in (0.0, 0.5, 0.9, 0.99, 0.9999):
+            R = T.phase_length(lam, n)
+            need = np.log(n) / (2 * np.sqrt(1 - lam))
+            assert R >= need and R - 1 < max(need, 1)
+            assert (1 - np.sqrt(1 - lam)) ** R <= n ** -0.5 + 1e-15
+    W0 = T.mixing_matrix(16, gen.edges_ring(16))
+    R1 = T.phase_length(T.spectrum(W0)[2], 16)
+    R100 = T.phase_length(T.spectrum(T.slack(W0, 0.01))[2], 16)
+    assert R1 == 7 and abs(R100 / R1 - 10) < 1.5
+    # the outer-variance term: r = e^8 gives log(r)/2 = 4 > log(16)/2
+    assert T.phase_length(0.75, 16, np.exp(8.0)) == 8
+    assert T.phase_length(0.75, 16, 1.0) == T.phase_length(0.75, 16) == 3     # log(16)/2 / 0.5 = 2.77
+
+
 def test_eta_formula():
     # eta = ((1-s)/(1+s)), s = sqrt(1-lambda^2); equivalently sqrt(eta) = lambda/(1+s)
     for lam in [0.0, 0.3, 0.804738, 0.99]:
