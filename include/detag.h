@@ -20,9 +20,15 @@
  *     valid once the stream reaches them.
  *   - Calls return a detag_status; nothing throws or aborts across the ABI.
  *     detag_last_error() gives the text of the last failure.
- *   - One context serves one stream at a time; calls on one context are not
- *     re-entrant.  State matrices passed to one call must not overlap unless
- *     the comment allows it.
+ *   - Calls on one context come from one host thread at a time.  Work of two
+ *     calls may run concurrently on two streams only if they use disjoint
+ *     context-owned scratch: detag_gossip_round, detag_accumulate,
+ *     detag_phase_end, detag_track, detag_grad_quadratic_diag and the on-chip
+ *     paths of detag_gossip_accel / detag_step / detag_dpsgd_step use none;
+ *     the per-round paths share one scratch area, the least-squares and
+ *     softmax gradients another, the two diagnostics a third.
+ *     State matrices passed to one call must not overlap unless the comment
+ *     allows it.
  */
 #ifndef DETAG_H
 #define DETAG_H
@@ -181,6 +187,40 @@ detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *G
  * in place on X (one plain gossip step of the models, then the local step).
  */
 detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, double alpha, void *stream);
+
+/*
+ * Algorithm 2 at the granularity it is printed in: one iteration = one step of
+ * accelerated gossip on the model replica and on the tracker (these calls, on
+ * a communication stream) while gradient queries at the phase-start model
+ * accumulate in the gradient buffer (detag_accumulate, on another stream); the
+ * last iteration of a phase ends with detag_phase_end.
+ *
+ * detag_gossip_round: one step of Algorithm 3,
+ *   Zout = (1+eta) * W^T Zcur - eta * Zprev.
+ * Zprev == Zcur for the first step of a phase (z_{-1} = z_0).  Zout may be the
+ * same buffer as Zprev (each output element reads only its own previous
+ * value); it must not be Zcur.  All three: n x ld, state type.  The caller
+ * rotates the buffers.  eta as in detag_gossip_accel.  With bf16 state every
+ * call rounds its output (the fused entry points round once per phase).
+ */
+detag_status detag_gossip_round(detag_ctx *ctx, const void *Zcur_dev, const void *Zprev_dev, void *Zout_dev,
+                                double eta, void *stream);
+
+/* Gradient buffer of Algorithm 2: Gacc += scale * g  (both fp32 n x ld; Gacc != g). */
+detag_status detag_accumulate(detag_ctx *ctx, float *Gacc_dev, const float *g_dev, double scale, void *stream);
+
+/*
+ * End of a phase of Algorithm 2 (its last four lines), with Xt the gossiped model
+ * replica and Y the gossiped tracker:
+ *   X <- Xt - alpha*Y;   Y <- Y + Gk - Gkm1;   Xt <- X;   Gkm1 <- 0.
+ * Gk holds the phase's accumulated gradients g(k), Gkm1 those of the phase
+ * before; on return Gkm1 is cleared, ready to be the next phase's accumulation
+ * buffer once the caller has swapped the two pointers (g(k-1) <- g(k), g(k) <- 0).
+ * X_dev, Xt_dev, Y_dev: state type; Gk_dev, Gkm1_dev: fp32.  X_dev may equal Xt_dev
+ * (no separate replica); otherwise the five must not overlap.
+ */
+detag_status detag_phase_end(detag_ctx *ctx, void *X_dev, void *Xt_dev, void *Y_dev, const float *Gk_dev,
+                             float *Gkm1_dev, double alpha, void *stream);
 
 /* Output of Algorithm 2: xbar[c] = (1/n) sum_i X[i,c].  xbar_dev: d floats. */
 detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream);

@@ -30,7 +30,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
                  "DETAG_EUNSUPPORTED", "DETAG_ENOMEM", "DETAG_EHIP"]
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
-           "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step",
+           "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
@@ -84,6 +84,12 @@ def lib() -> C.CDLL:
     L.detag_step.restype = C.c_int
     L.detag_dpsgd_step.argtypes = [vp, vp, vp, f64, vp]
     L.detag_dpsgd_step.restype = C.c_int
+    L.detag_gossip_round.argtypes = [vp, vp, vp, vp, f64, vp]
+    L.detag_gossip_round.restype = C.c_int
+    L.detag_accumulate.argtypes = [vp, vp, vp, f64, vp]
+    L.detag_accumulate.restype = C.c_int
+    L.detag_phase_end.argtypes = [vp, vp, vp, vp, vp, vp, f64, vp]
+    L.detag_phase_end.restype = C.c_int
     L.detag_mean.argtypes = [vp, vp, vp, vp]
     L.detag_mean.restype = C.c_int
     L.detag_consensus_error.argtypes = [vp, vp, vp, vp]
@@ -270,6 +276,22 @@ class Context:
         self._check(lib().detag_dpsgd_step(self._h, self._state(X, "X"), self._mat(G, torch.float32, "G"), alpha,
                                            self._stream()))
 
+    # -- Algorithm 2 iteration by iteration ---------------------------------------
+    def gossip_round(self, Z_cur, Z_prev, Z_out, eta: float = -1.0):
+        self._check(lib().detag_gossip_round(self._h, self._state(Z_cur, "Z_cur"), self._state(Z_prev, "Z_prev"),
+                                             self._state(Z_out, "Z_out"), eta, self._stream()))
+
+    def accumulate(self, G_acc, g, scale: float = 1.0):
+        import torch
+        self._check(lib().detag_accumulate(self._h, self._mat(G_acc, torch.float32, "G_acc"),
+                                           self._mat(g, torch.float32, "g"), scale, self._stream()))
+
+    def phase_end(self, X, X_tilde, Y, G_k, G_km1, alpha: float):
+        import torch
+        self._check(lib().detag_phase_end(self._h, self._state(X, "X"), self._state(X_tilde, "X_tilde"),
+                                          self._state(Y, "Y"), self._mat(G_k, torch.float32, "G_k"),
+                                          self._mat(G_km1, torch.float32, "G_km1"), alpha, self._stream()))
+
     # -- diagnostics -----------------------------------------------------------
     def mean(self, X, out=None):
         import torch
@@ -369,6 +391,9 @@ def detag_track(ctx: Context, Y, G_new, G_old): ctx.track(Y, G_new, G_old)
 def detag_step(ctx: Context, X, Y, G_new, G_old, alpha, K, eta=-1.0, variant=DETAG_VARIANT_ATC):
     ctx.step(X, Y, G_new, G_old, alpha, K, eta, variant)
 def detag_dpsgd_step(ctx: Context, X, G, alpha): ctx.dpsgd_step(X, G, alpha)
+def detag_gossip_round(ctx: Context, Z_cur, Z_prev, Z_out, eta=-1.0): ctx.gossip_round(Z_cur, Z_prev, Z_out, eta)
+def detag_accumulate(ctx: Context, G_acc, g, scale=1.0): ctx.accumulate(G_acc, g, scale)
+def detag_phase_end(ctx: Context, X, X_tilde, Y, G_k, G_km1, alpha): ctx.phase_end(X, X_tilde, Y, G_k, G_km1, alpha)
 def detag_mean(ctx: Context, X, out=None): return ctx.mean(X, out)
 def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error(X, out)
 def detag_grad_quadratic_diag(ctx: Context, X, h, b, G, noise=None, sigma=0.0, seed=0, step=0):

@@ -423,6 +423,47 @@ detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, d
   return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
 }
 
+detag_status detag_gossip_round(detag_ctx *ctx, const void *Zcur_dev, const void *Zprev_dev, void *Zout_dev, double eta,
+                                void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, Zcur_dev, "Zcur_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Zprev_dev, "Zprev_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Zout_dev, "Zout_dev")) return st;
+  if (Zout_dev == Zcur_dev) return set_err(ctx, DETAG_EINVAL, "Zout must not be Zcur: every neighbour reads Zcur");
+  float e;
+  if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
+  const int rc = launch_gossip_round(ctx->shape, dev_csr(ctx), Zcur_dev, Zprev_dev, Zout_dev, e, stream);
+  return rc ? hip_fail(ctx, "gossip round", rc) : DETAG_OK;
+}
+
+detag_status detag_accumulate(detag_ctx *ctx, float *Gacc_dev, const float *g_dev, double scale, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gacc_dev, "Gacc_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, g_dev, "g_dev")) return st;
+  if (Gacc_dev == g_dev) return set_err(ctx, DETAG_EINVAL, "Gacc and g must not overlap");
+  if (!std::isfinite(scale)) return set_err(ctx, DETAG_EINVAL, "scale must be finite");
+  const int rc = launch_accumulate(ctx->shape, Gacc_dev, g_dev, float(scale), stream);
+  return rc ? hip_fail(ctx, "accumulate", rc) : DETAG_OK;
+}
+
+detag_status detag_phase_end(detag_ctx *ctx, void *X_dev, void *Xt_dev, void *Y_dev, const float *Gk_dev,
+                             float *Gkm1_dev, double alpha, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Xt_dev, "Xt_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Y_dev, "Y_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gk_dev, "Gk_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, Gkm1_dev, "Gkm1_dev")) return st;
+  const void *p[5] = {X_dev, Xt_dev, Y_dev, Gk_dev, Gkm1_dev};
+  for (int a = 0; a < 5; ++a)
+    for (int b = a + 1; b < 5; ++b)
+      if (p[a] == p[b] && !(a == 0 && b == 1))
+        return set_err(ctx, DETAG_EINVAL, "the buffers must not overlap (X may be Xt)");
+  if (!std::isfinite(alpha)) return set_err(ctx, DETAG_EINVAL, "alpha must be finite");
+  const int rc = launch_phase_end(ctx->shape, X_dev, Xt_dev, Y_dev, Gk_dev, Gkm1_dev, float(alpha), stream);
+  return rc ? hip_fail(ctx, "phase end", rc) : DETAG_OK;
+}
+
 detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
@@ -507,7 +548,7 @@ detag_status detag_grad_softmax_bf16(detag_ctx *ctx, const void *X_dev, const ui
     return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient limits: 2 <= C <= 10, F % 32 == 0, B % 32 == 0, B <= 256");
   if (int64_t(C) * F + C != ctx->shape.d)
     return set_err(ctx, DETAG_EINVAL, "d must equal C*F + C");
-  if (detag_status st = need_grad_scratch(ctx, softmax_scratch_floats(ctx->shape.n, C, B))) return st;
+  if (detag_status st = need_grad_scratch(ctx, softmax_scratch_floats(ctx->shape.n, C, B, F))) return st;
   const int rc = launch_grad_softmax(ctx->shape, X_dev, feat_dev, labels_dev, batch_dev, S, F, C, B, ctx->d_resid,
                                      G_dev, loss_dev, stream);
   return rc ? hip_fail(ctx, "softmax gradient", rc) : DETAG_OK;

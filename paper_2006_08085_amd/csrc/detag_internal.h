@@ -78,6 +78,11 @@ int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const
 int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
                  void *stream);
 int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream);
+// Gacc += scale * g (fp32 n x ld)
+int launch_accumulate(const Shape &s, float *Gacc, const float *g, float scale, void *stream);
+// X = Xt - alpha*Y; Y += Gk - Gkm1; Xt = X; Gkm1 = 0   (X may be Xt)
+int launch_phase_end(const Shape &s, void *X, void *Xt, void *Y, const float *Gk, float *Gkm1, float alpha,
+                     void *stream);
 // n x ld matrices: bf16 -> fp32 (exact) and fp32 -> bf16 (round to nearest even)
 int launch_widen(const Shape &s, const void *src_bf16, float *dst, void *stream);
 int launch_narrow(const Shape &s, const float *src, void *dst_bf16, void *stream);
@@ -105,7 +110,7 @@ int launch_grad_quadratic(const Shape &s, const void *X, const float *h, int h_p
                           void *stream);
 int launch_grad_lstsq(const Shape &s, const void *X, const float *A, const float *b, int m, float *resid,
                       float *G, void *stream);
-int64_t softmax_scratch_floats(int n, int C, int B);
+int64_t softmax_scratch_floats(int n, int C, int B, int F);
 int launch_grad_softmax(const Shape &s, const void *X, const uint16_t *feat, const int32_t *labels,
                         const int32_t *batch, int S, int F, int C, int B, float *scratch, float *G, float *loss,
                         void *stream);

@@ -136,6 +136,47 @@ __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_
   }
 }
 
+// Gacc += scale * g
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void accumulate_kernel(int64_t d, int64_t ld, float *Gacc,
+                                                              const float *__restrict__ g, float scale) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int64_t off = int64_t(blockIdx.y) * ld + c0;
+  float a[VEC], x[VEC];
+  load_vec<float, VEC>(Gacc + off, valid, a);
+  load_vec<float, VEC>(g + off, valid, x);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = fmaf(scale, x[e], a[e]);
+  store_vec<float, VEC>(Gacc + off, valid, a);
+}
+
+// End of a phase of Algorithm 2: X = Xt - alpha*Y; Y += Gk - Gkm1; Xt = X; Gkm1 = 0.
+template <typename ST, int VEC>
+__global__ __launch_bounds__(kThreads) void phase_end_kernel(int64_t d, int64_t ld, ST *X, ST *Xt, ST *Y,
+                                                             const float *__restrict__ Gk, float *Gkm1, float alpha) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int64_t off = int64_t(blockIdx.y) * ld + c0;
+  float x[VEC], y[VEC], gk[VEC], gm[VEC];
+  load_vec<ST, VEC>(Xt + off, valid, x);
+  load_vec<ST, VEC>(Y + off, valid, y);
+  load_vec<float, VEC>(Gk + off, valid, gk);
+  load_vec<float, VEC>(Gkm1 + off, valid, gm);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    x[e] = fmaf(-alpha, y[e], x[e]);
+    y[e] = y[e] + gk[e] - gm[e];
+    gm[e] = 0.f;
+  }
+  store_vec<ST, VEC>(X + off, valid, x);
+  if (Xt != X) store_vec<ST, VEC>(Xt + off, valid, x);
+  store_vec<ST, VEC>(Y + off, valid, y);
+  store_vec<float, VEC>(Gkm1 + off, valid, gm);
+}
+
 // dst = src with a change of storage type (bf16 -> fp32 exact, fp32 -> bf16 round to nearest even)
 template <typename TS, typename TD, int VEC>
 __global__ __launch_bounds__(kThreads) void convert_kernel(int64_t d, int64_t ld, const TS *__restrict__ src,
@@ -221,6 +262,36 @@ int launch_convert_t(const Shape &s, const void *src, void *dst, void *stream) {
 }
 
 }  // namespace
+
+int launch_accumulate(const Shape &s, float *Gacc, const float *g, float scale, void *stream) {
+  const bool vec = vec_ok(s, {}, {Gacc, g});
+  dim3 grid(ceil_div_i64(s.d, kThreads * (vec ? 4 : 1)), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec) accumulate_kernel<4><<<grid, kThreads, 0, st>>>(s.d, s.ld, Gacc, g, scale);
+  else accumulate_kernel<1><<<grid, kThreads, 0, st>>>(s.d, s.ld, Gacc, g, scale);
+  return hip_rc(hipGetLastError());
+}
+
+template <typename ST>
+int launch_phase_end_t(const Shape &s, void *X, void *Xt, void *Y, const float *Gk, float *Gkm1, float alpha,
+                       void *stream) {
+  const bool vec = vec_ok(s, {X, Xt, Y}, {Gk, Gkm1});
+  dim3 grid(ceil_div_i64(s.d, kThreads * (vec ? 4 : 1)), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    phase_end_kernel<ST, 4><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X), static_cast<ST *>(Xt),
+                                                       static_cast<ST *>(Y), Gk, Gkm1, alpha);
+  else
+    phase_end_kernel<ST, 1><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X), static_cast<ST *>(Xt),
+                                                       static_cast<ST *>(Y), Gk, Gkm1, alpha);
+  return hip_rc(hipGetLastError());
+}
+
+int launch_phase_end(const Shape &s, void *X, void *Xt, void *Y, const float *Gk, float *Gkm1, float alpha,
+                     void *stream) {
+  return s.bf16 ? launch_phase_end_t<bf16_t>(s, X, Xt, Y, Gk, Gkm1, alpha, stream)
+                : launch_phase_end_t<float>(s, X, Xt, Y, Gk, Gkm1, alpha, stream);
+}
 
 int launch_widen(const Shape &s, const void *src_bf16, float *dst, void *stream) {
   return launch_convert_t<bf16_t, float>(s, src_bf16, dst, stream);

@@ -136,3 +136,51 @@ def test_spectral_gap_sweep_on_the_quadratic(golden_dir):
         seq = [ce[k, name] for k in (1.0, 0.1, 0.05, 0.01)]
         assert all(a < b_ for a, b_ in zip(seq, seq[1:]))
     assert ce[0.01, "dsgt"] > 20 * ce[1.0, "dsgt"]
+
+
+def test_by_phase_form_is_the_phase_form_with_summed_queries():
+    """Algorithm 2 run iteration by iteration (one gossip step and B gradient queries per iteration) ends every
+    phase exactly where the phase-at-a-time step lands when it is given the sum of that phase's R*B gradients
+    - two separately written routes through the same algorithm (this one uses dense W^T products and explicit
+    recursion state, the other the neighbour lists)."""
+    n, d, alpha, Rlen, B = 6, 5, 0.07, 3, 2
+    W = 0.5 * np.eye(n) + 0.5 * np.roll(np.eye(n), 1, axis=1)          # asymmetric
+    eta = 0.3
+    h, b = np.linspace(0.5, 1.5, d), gen.state(n, d, 5).astype(np.float64)
+    rng = np.random.default_rng(0)
+    noise = rng.standard_normal((4 * Rlen, B, n, d))
+    g = lambda t, q, X: O.grad_quadratic_diag(X, h, b) + 0.1 * noise[t, q]
+    Xb, Yb, phases = R.by_phase(g, np.zeros((n, d)), W, alpha, 4 * Rlen, Rlen, eta, B=B)
+    assert phases == 4
+    X = np.zeros((n, d)); Y = np.zeros((n, d)); Go = np.zeros((n, d))
+    for k in range(4):
+        Gn = sum(g(k * Rlen + r, q, X) for r in range(Rlen) for q in range(B))
+        X, Y = G.detag_step(X, Y, Gn, Go, W, alpha, Rlen, eta, "alg2")
+        Go = Gn
+    assert np.allclose(Xb, X, atol=1e-13) and np.allclose(Yb, Y, atol=1e-13)
+    # the tracker's mean is the mean of the last completed buffer; iterations of an unfinished phase change nothing
+    assert np.allclose(Yb.mean(0), Go.mean(0), atol=1e-13)
+    Xc, _, ph = R.by_phase(g, np.zeros((n, d)), W, alpha, 4 * Rlen - 1, Rlen, eta, B=B)
+    Xd, _, _ = R.by_phase(g, np.zeros((n, d)), W, alpha, 3 * Rlen, Rlen, eta, B=B)
+    assert ph == 3 and np.array_equal(Xc, Xd)
+
+
+def test_dynamic_phase_length_starts_as_dsgt():
+    """Phase length 1 with eta = 0 for the first phases is DSGT (in the printed, gossip-then-correct order);
+    afterwards the longer phases take over from that state."""
+    n, d, alpha = 6, 4, 0.1
+    W = T.mixing_matrix(n, gen.edges_ring(n))
+    eta = T.eta_from_lambda(T.spectrum(W)[2])
+    h, b = np.linspace(0.5, 1.5, d), gen.state(n, d, 5).astype(np.float64)
+    g = lambda t, q, X: O.grad_quadratic_diag(X, h, b)
+    sched_R = lambda k: 1 if k < 5 else 3
+    sched_eta = lambda k: 0.0 if k < 5 else eta
+    Xa, Ya, ph = R.by_phase(g, np.zeros((n, d)), W, alpha, 5 + 3 * 4, sched_R, sched_eta)
+    assert ph == 9
+    X = np.zeros((n, d)); Y = np.zeros((n, d)); Go = np.zeros((n, d))
+    for k in range(9):
+        Rk = sched_R(k)
+        Gn = Rk * g(0, 0, X)
+        X, Y = G.detag_step(X, Y, Gn, Go, W, alpha, Rk, sched_eta(k), "alg2")
+        Go = Gn
+    assert np.allclose(Xa, X, atol=1e-13) and np.allclose(Ya, Y, atol=1e-13)
