@@ -222,6 +222,39 @@ detag_status detag_accumulate(detag_ctx *ctx, float *Gacc_dev, const float *g_de
 detag_status detag_phase_end(detag_ctx *ctx, void *X_dev, void *Xt_dev, void *Y_dev, const float *Gk_dev,
                              float *Gkm1_dev, double alpha, void *stream);
 
+/*
+ * DeFacto (Algorithm 1) and the exact average consensus it communicates with
+ * (Lemma 1): a sequence of R matrices with the sparsity of the context's graph
+ * whose product is 11^T/n.  The factors are the spanning-tree construction of
+ * the paper's supplementary material (gather to a root level by level, then
+ * propagate back), built on the host at creation: R = 2 * (depth of the
+ * breadth-first tree from `root`), between D and 2D for a graph of diameter D.
+ * Factor r is stored as a CSR whose row i lists (j, A_ij), j ascending, and is
+ * applied as  z_i <- sum_j A_ij z_j,  i.e. A_ij = [W_r]_ji in Algorithm 1's
+ * notation; applying r = 0, ..., R-1 in order leaves every worker with the mean.
+ */
+typedef struct detag_factors detag_factors;
+
+/* Builds the factors for the graph of ctx's W (undirected support of its off-diagonal entries).
+ * The factors belong to ctx's device and must be destroyed before ctx.  DETAG_EINVAL for a bad root. */
+detag_status detag_factors_create(detag_ctx *ctx, int32_t root, detag_factors **out);
+void detag_factors_destroy(detag_factors *f);
+/* Number of factors R. */
+detag_status detag_factors_count(const detag_factors *f, int32_t *R);
+/* Host view of factor r (arrays live until detag_factors_destroy). */
+detag_status detag_factors_get_csr(const detag_factors *f, int32_t r, int64_t *nnz, const int32_t **rowptr,
+                                   const int32_t **colidx, const double **vals);
+/* Zout = A_r Zin: the communication step of Algorithm 1 with the r-th factor.  n x ld, state type; Zout != Zin. */
+detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t r, const void *Zin_dev,
+                                void *Zout_dev, void *stream);
+/*
+ * End of a round of Algorithm 1: X <- Xt - scale*G;  Xt <- X;  G <- 0,
+ * with Xt the averaged model copy, G the gradient buffer and scale = alpha/R.
+ * X_dev, Xt_dev: state type (X_dev may equal Xt_dev); G_dev: fp32.
+ */
+detag_status detag_defacto_update(detag_ctx *ctx, void *X_dev, void *Xt_dev, float *G_dev, double scale,
+                                  void *stream);
+
 /* Output of Algorithm 2: xbar[c] = (1/n) sum_i X[i,c].  xbar_dev: d floats. */
 detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream);
 

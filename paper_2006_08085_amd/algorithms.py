@@ -12,7 +12,7 @@ from __future__ import annotations
 
 from typing import Callable, Dict, List, Optional
 
-from .binding import Context, DETAG_VARIANT_ATC
+from .binding import Context, Factors, DETAG_VARIANT_ATC
 from .memory import new_matrix
 
 ALGORITHMS = ("detag", "dsgt", "dpsgd")
@@ -170,3 +170,30 @@ def run_by_phase(ctx: Context, grad: Callable, X, alpha: float, T: int, R, eta=-
         for _ in range(min(Rk, T - bp.t)):
             bp.iteration(Rk, ek)
     return bp
+
+
+def run_defacto(ctx: Context, factors: Factors, grad: Callable, X, alpha: float, T: int, B: int = 1) -> int:
+    """T iterations of Algorithm 1 (DeFacto) in place on X.  A round is 2R iterations, R = factors.R: R
+    iterations of B gradient queries each at the round-start model, added to the gradient buffer; R iterations
+    that multiply the model copy by the factors of the exact average consensus, one per iteration; then
+    x <- copy - alpha * g / R.  grad(t, q, X, g) as in ByPhase.  An unfinished round leaves X at the last round
+    end.  Returns the number of completed rounds."""
+    import torch
+    n, d, ld, dev, R = ctx.n, ctx.d, ctx.ld, X.device, factors.R
+    G = new_matrix(n, d, ld, device=dev)
+    g = new_matrix(n, d, ld, device=dev)
+    xt = [X.clone(), new_matrix(n, d, ld, dtype=X.dtype, device=dev)]
+    rounds = 0
+    for t in range(T):
+        r = t % (2 * R) if R else 0
+        if r < R:
+            for q in range(B):
+                grad(t, q, X, g)
+                ctx.accumulate(G, g, 1.0)
+        else:
+            factors.apply(r - R, xt[0], xt[1])
+            xt[0], xt[1] = xt[1], xt[0]
+        if r == 2 * R - 1:
+            ctx.defacto_update(X, xt[0], G, alpha / R)
+            rounds += 1
+    return rounds

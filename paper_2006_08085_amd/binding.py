@@ -31,6 +31,8 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
            "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
+           "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
+           "detag_factor_apply", "detag_defacto_update",
            "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
@@ -90,6 +92,19 @@ def lib() -> C.CDLL:
     L.detag_accumulate.restype = C.c_int
     L.detag_phase_end.argtypes = [vp, vp, vp, vp, vp, vp, f64, vp]
     L.detag_phase_end.restype = C.c_int
+    L.detag_factors_create.argtypes = [vp, i32, C.POINTER(vp)]
+    L.detag_factors_create.restype = C.c_int
+    L.detag_factors_destroy.argtypes = [vp]
+    L.detag_factors_destroy.restype = None
+    L.detag_factors_count.argtypes = [vp, C.POINTER(i32)]
+    L.detag_factors_count.restype = C.c_int
+    L.detag_factors_get_csr.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.POINTER(i32)), C.POINTER(C.POINTER(i32)),
+                                        C.POINTER(C.POINTER(f64))]
+    L.detag_factors_get_csr.restype = C.c_int
+    L.detag_factor_apply.argtypes = [vp, vp, i32, vp, vp, vp]
+    L.detag_factor_apply.restype = C.c_int
+    L.detag_defacto_update.argtypes = [vp, vp, vp, vp, f64, vp]
+    L.detag_defacto_update.restype = C.c_int
     L.detag_mean.argtypes = [vp, vp, vp, vp]
     L.detag_mean.restype = C.c_int
     L.detag_consensus_error.argtypes = [vp, vp, vp, vp]
@@ -176,6 +191,46 @@ class Topology:
         t.colidx = ptr(self.colidx, C.c_int32)
         t.vals = ptr(self.vals, C.c_double)
         return t
+
+
+class Factors:
+    """Owns one detag_factors: the matrices of the exact average consensus on a context's graph."""
+
+    def __init__(self, ctx: "Context", root: int = 0):
+        h = C.c_void_p()
+        ctx._check(lib().detag_factors_create(ctx._h, root, C.byref(h)))
+        self._h, self.ctx = h, ctx
+        R = C.c_int32()
+        ctx._check(lib().detag_factors_count(self._h, C.byref(R)))
+        self.R = R.value
+
+    def close(self):
+        if self._h:
+            lib().detag_factors_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def dense(self, r: int) -> np.ndarray:
+        """Factor r as a dense n x n array A (z <- A z), rebuilt from detag_factors_get_csr."""
+        n = self.ctx.n
+        nnz = C.c_int64()
+        rp, ci, va = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)(), C.POINTER(C.c_double)()
+        self.ctx._check(lib().detag_factors_get_csr(self._h, r, C.byref(nnz), C.byref(rp), C.byref(ci), C.byref(va)))
+        A = np.zeros((n, n))
+        for i in range(n):
+            for k in range(rp[i], rp[i + 1]):
+                A[i, ci[k]] = va[k]
+        return A
+
+    def apply(self, r: int, Z_in, Z_out):
+        c = self.ctx
+        c._check(lib().detag_factor_apply(c._h, self._h, r, c._state(Z_in, "Z_in"), c._state(Z_out, "Z_out"),
+                                          c._stream()))
 
 
 class Context:
@@ -292,6 +347,11 @@ class Context:
                                           self._state(Y, "Y"), self._mat(G_k, torch.float32, "G_k"),
                                           self._mat(G_km1, torch.float32, "G_km1"), alpha, self._stream()))
 
+    def defacto_update(self, X, X_tilde, G, scale: float):
+        import torch
+        self._check(lib().detag_defacto_update(self._h, self._state(X, "X"), self._state(X_tilde, "X_tilde"),
+                                               self._mat(G, torch.float32, "G"), scale, self._stream()))
+
     # -- diagnostics -----------------------------------------------------------
     def mean(self, X, out=None):
         import torch
@@ -394,6 +454,12 @@ def detag_dpsgd_step(ctx: Context, X, G, alpha): ctx.dpsgd_step(X, G, alpha)
 def detag_gossip_round(ctx: Context, Z_cur, Z_prev, Z_out, eta=-1.0): ctx.gossip_round(Z_cur, Z_prev, Z_out, eta)
 def detag_accumulate(ctx: Context, G_acc, g, scale=1.0): ctx.accumulate(G_acc, g, scale)
 def detag_phase_end(ctx: Context, X, X_tilde, Y, G_k, G_km1, alpha): ctx.phase_end(X, X_tilde, Y, G_k, G_km1, alpha)
+def detag_factors_create(ctx: Context, root=0): return Factors(ctx, root)
+def detag_factors_destroy(f: Factors): f.close()
+def detag_factors_count(f: Factors): return f.R
+def detag_factors_get_csr(f: Factors, r): return f.dense(r)
+def detag_factor_apply(ctx: Context, f: Factors, r, Z_in, Z_out): f.apply(r, Z_in, Z_out)
+def detag_defacto_update(ctx: Context, X, X_tilde, G, scale): ctx.defacto_update(X, X_tilde, G, scale)
 def detag_mean(ctx: Context, X, out=None): return ctx.mean(X, out)
 def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error(X, out)
 def detag_grad_quadratic_diag(ctx: Context, X, h, b, G, noise=None, sigma=0.0, seed=0, step=0):

@@ -34,6 +34,15 @@ struct detag_ctx {
   mutable std::string err;
 };
 
+struct detag_factors {
+  detag_ctx *ctx = nullptr;
+  std::vector<HostFactor> host;
+  // device copies, all factors back to back: rowptr R*(n+1), colidx / vals at offs[r]
+  int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
+  float *d_vals = nullptr;
+  std::vector<int64_t> offs;
+};
+
 namespace {
 
 thread_local std::string g_create_err;
@@ -462,6 +471,102 @@ detag_status detag_phase_end(detag_ctx *ctx, void *X_dev, void *Xt_dev, void *Y_
   if (!std::isfinite(alpha)) return set_err(ctx, DETAG_EINVAL, "alpha must be finite");
   const int rc = launch_phase_end(ctx->shape, X_dev, Xt_dev, Y_dev, Gk_dev, Gkm1_dev, float(alpha), stream);
   return rc ? hip_fail(ctx, "phase end", rc) : DETAG_OK;
+}
+
+detag_status detag_factors_create(detag_ctx *ctx, int32_t root, detag_factors **out) {
+  if (out) *out = nullptr;
+  if (!ctx || !out) return set_err(ctx, DETAG_EINVAL, "ctx or out is NULL");
+  auto *f = new (std::nothrow) detag_factors;
+  if (!f) return set_err(ctx, DETAG_ENOMEM, "out of host memory");
+  f->ctx = ctx;
+  std::string err;
+  if (!build_consensus_factors(ctx->W, root, f->host, err)) {
+    delete f;
+    return set_err(ctx, DETAG_EINVAL, err);
+  }
+  const int n = ctx->W.n, R = int(f->host.size());
+  int64_t nnz = 0;
+  for (auto &h : f->host) f->offs.push_back(nnz), nnz += int64_t(h.colidx.size());
+  if (ctx->has_device && R > 0) {
+    std::vector<int32_t> rp, ci;
+    std::vector<float> va;
+    for (auto &h : f->host) {
+      rp.insert(rp.end(), h.rowptr.begin(), h.rowptr.end());
+      ci.insert(ci.end(), h.colidx.begin(), h.colidx.end());
+      for (double v : h.vals) va.push_back(float(v));
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&f->d_rowptr), rp.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_colidx), ci.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_vals), va.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(f->d_rowptr, rp.data(), rp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(f->d_colidx, ci.data(), ci.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(f->d_vals, va.data(), va.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      detag_factors_destroy(f);
+      return hip_fail(ctx, "factor upload", int(e));
+    }
+    (void)n;
+  }
+  *out = f;
+  return DETAG_OK;
+}
+
+void detag_factors_destroy(detag_factors *f) {
+  if (!f) return;
+  if (f->d_rowptr || f->d_colidx || f->d_vals) {
+    (void)hipDeviceSynchronize();
+    (void)hipFree(f->d_rowptr);
+    (void)hipFree(f->d_colidx);
+    (void)hipFree(f->d_vals);
+  }
+  delete f;
+}
+
+detag_status detag_factors_count(const detag_factors *f, int32_t *R) {
+  if (!f || !R) return DETAG_EINVAL;
+  *R = int32_t(f->host.size());
+  return DETAG_OK;
+}
+
+detag_status detag_factors_get_csr(const detag_factors *f, int32_t r, int64_t *nnz, const int32_t **rowptr,
+                                   const int32_t **colidx, const double **vals) {
+  if (!f) return DETAG_EINVAL;
+  if (r < 0 || r >= int32_t(f->host.size())) return set_err(f->ctx, DETAG_EINVAL, "factor index out of range");
+  const HostFactor &h = f->host[r];
+  if (nnz) *nnz = int64_t(h.colidx.size());
+  if (rowptr) *rowptr = h.rowptr.data();
+  if (colidx) *colidx = h.colidx.data();
+  if (vals) *vals = h.vals.data();
+  return DETAG_OK;
+}
+
+detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t r, const void *Zin_dev,
+                                void *Zout_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (!f || f->ctx != ctx) return set_err(ctx, DETAG_EINVAL, "the factors were not built for this context");
+  if (r < 0 || r >= int32_t(f->host.size())) return set_err(ctx, DETAG_EINVAL, "factor index out of range");
+  if (detag_status st = check_state_ptr(ctx, Zin_dev, "Zin_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Zout_dev, "Zout_dev")) return st;
+  if (Zin_dev == Zout_dev) return set_err(ctx, DETAG_EINVAL, "Zout must not be Zin");
+  DevCsr a;
+  a.rowptr = f->d_rowptr + int64_t(r) * (ctx->W.n + 1);
+  a.colidx = f->d_colidx + f->offs[r];
+  a.vals = f->d_vals + f->offs[r];
+  const int rc = launch_spmm(ctx->shape, a, Zin_dev, Zout_dev, stream);
+  return rc ? hip_fail(ctx, "factor apply", rc) : DETAG_OK;
+}
+
+detag_status detag_defacto_update(detag_ctx *ctx, void *X_dev, void *Xt_dev, float *G_dev, double scale, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (detag_status st = check_state_ptr(ctx, Xt_dev, "Xt_dev")) return st;
+  if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
+  if (static_cast<void *>(G_dev) == X_dev || static_cast<void *>(G_dev) == Xt_dev)
+    return set_err(ctx, DETAG_EINVAL, "G must not overlap the models");
+  if (!std::isfinite(scale)) return set_err(ctx, DETAG_EINVAL, "scale must be finite");
+  const int rc = launch_defacto_update(ctx->shape, X_dev, Xt_dev, G_dev, float(scale), stream);
+  return rc ? hip_fail(ctx, "defacto update", rc) : DETAG_OK;
 }
 
 detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void *stream) {

@@ -30,6 +30,15 @@ struct HostW {
 // Builds, validates and analyses W.  On failure returns the status and fills err.
 detag_status build_gossip_matrix(const detag_topology *topo, int n, HostW &W, std::string &err);
 
+// One factor of the average-consensus product, as a CSR whose row i lists (j, A_ij), j ascending:
+// applying it is x_i <- sum_j A_ij x_j (in Algorithm 1's notation A_ij = [W_r]_ji).
+struct HostFactor {
+  std::vector<int32_t> rowptr, colidx;
+  std::vector<double> vals;
+};
+// Spanning-tree (gather, then propagate) factors on the undirected support of W, rooted at `root`.
+bool build_consensus_factors(const HostW &W, int root, std::vector<HostFactor> &out, std::string &err);
+
 // Eigenvalues (ascending) of a dense symmetric matrix, cyclic Jacobi. a is n*n row-major, destroyed.
 void symmetric_eigenvalues(std::vector<double> &a, int n, std::vector<double> &ev);
 
@@ -50,8 +59,8 @@ struct DevCsr {
 // Neighbour table of the on-chip kernel for arbitrary W (256 row slots, wavefront-major: row i sits at slot
 // (i % 16) * 16 + i / 16).  Per slot: deg/2 words of packed 16-bit LDS byte offsets of the neighbours' rows, then
 // the off-diagonal weights as fp32 bit patterns (one word if every row has equal off-diagonal weights, else deg
-// words), then W_ii.  Missing neighbours point at the row itself with weight 0 (general) or are folded into the
-// self weight (uniform).
+// words).  Missing neighbours point at the row itself: the kernel works with differences z_j - z_i, so they
+// contribute nothing.
 struct EllHost {
   int deg = 0;            // table width: 2, 4 or 8
   bool uniform = false;   // each row's off-diagonal weights are all equal
@@ -66,6 +75,10 @@ struct Shape {
   bool bf16;  // storage of X/Y
 };
 
+// out = A cur for a CSR matrix A whose rows need not sum to one (row i lists (j, A_ij)); out != cur.
+int launch_spmm(const Shape &s, const DevCsr &a, const void *cur, void *out, void *stream);
+// X = Xt - scale*G; Xt = X; G = 0   (X may be Xt)
+int launch_defacto_update(const Shape &s, void *X, void *Xt, float *G, float scale, void *stream);
 // One round of Algorithm 3, out = (1+eta) * (W^T cur) - eta * prev.  out may alias prev; out != cur.
 int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float eta,
                         void *stream);

@@ -136,6 +136,55 @@ __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_
   }
 }
 
+// out[i,:] = sum_k vals[k] * cur[col[k],:] for a general sparse matrix (rows need not sum to one, may be empty):
+// the factor matrices of the exact average consensus (Lemma 1).
+template <typename ST, int VEC>
+__global__ __launch_bounds__(kThreads) void spmm_kernel(int n, int64_t d, int64_t ld, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ colidx,
+                                                        const float *__restrict__ vals, const ST *__restrict__ cur,
+                                                        ST *__restrict__ out, int rows_per_group) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int r0 = blockIdx.y * rows_per_group;
+  const int r1 = r0 + rows_per_group < n ? r0 + rows_per_group : n;
+  for (int i = r0; i < r1; ++i) {
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    const int k1 = rowptr[i + 1];
+    for (int k = rowptr[i]; k < k1; ++k) {
+      const float w = vals[k];
+      float v[VEC];
+      load_vec<ST, VEC>(cur + int64_t(colidx[k]) * ld + c0, valid, v);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(w, v[e], acc[e]);
+    }
+    store_vec<ST, VEC>(out + int64_t(i) * ld + c0, valid, acc);
+  }
+}
+
+// End of a round of Algorithm 1: X = Xt - scale*G; Xt = X; G = 0.
+template <typename ST, int VEC>
+__global__ __launch_bounds__(kThreads) void defacto_update_kernel(int64_t d, int64_t ld, ST *X, ST *Xt, float *G,
+                                                                  float scale) {
+  const int64_t c0 = (int64_t(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+  if (c0 >= d) return;
+  const int valid = int(d - c0 < VEC ? d - c0 : VEC);
+  const int64_t off = int64_t(blockIdx.y) * ld + c0;
+  float x[VEC], g[VEC];
+  load_vec<ST, VEC>(Xt + off, valid, x);
+  load_vec<float, VEC>(G + off, valid, g);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    x[e] = fmaf(-scale, g[e], x[e]);
+    g[e] = 0.f;
+  }
+  store_vec<ST, VEC>(X + off, valid, x);
+  if (Xt != X) store_vec<ST, VEC>(Xt + off, valid, x);
+  store_vec<float, VEC>(G + off, valid, g);
+}
+
 // Gacc += scale * g
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void accumulate_kernel(int64_t d, int64_t ld, float *Gacc,
@@ -262,6 +311,45 @@ int launch_convert_t(const Shape &s, const void *src, void *dst, void *stream) {
 }
 
 }  // namespace
+
+template <typename ST>
+int launch_spmm_t(const Shape &s, const DevCsr &a, const void *cur, void *out, void *stream) {
+  const bool vec = vec_ok(s, {cur, out}, {});
+  const int col_blocks = ceil_div_i64(s.d, kThreads * (vec ? 4 : 1));
+  const int rpg = rows_per_group_for(s, col_blocks);
+  dim3 grid(col_blocks, (s.n + rpg - 1) / rpg);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    spmm_kernel<ST, 4><<<grid, kThreads, 0, st>>>(s.n, s.d, s.ld, a.rowptr, a.colidx, a.vals,
+                                                  static_cast<const ST *>(cur), static_cast<ST *>(out), rpg);
+  else
+    spmm_kernel<ST, 1><<<grid, kThreads, 0, st>>>(s.n, s.d, s.ld, a.rowptr, a.colidx, a.vals,
+                                                  static_cast<const ST *>(cur), static_cast<ST *>(out), rpg);
+  return hip_rc(hipGetLastError());
+}
+
+int launch_spmm(const Shape &s, const DevCsr &a, const void *cur, void *out, void *stream) {
+  return s.bf16 ? launch_spmm_t<bf16_t>(s, a, cur, out, stream) : launch_spmm_t<float>(s, a, cur, out, stream);
+}
+
+template <typename ST>
+int launch_defacto_update_t(const Shape &s, void *X, void *Xt, float *G, float scale, void *stream) {
+  const bool vec = vec_ok(s, {X, Xt}, {G});
+  dim3 grid(ceil_div_i64(s.d, kThreads * (vec ? 4 : 1)), s.n);
+  auto st = static_cast<hipStream_t>(stream);
+  if (vec)
+    defacto_update_kernel<ST, 4><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X), static_cast<ST *>(Xt), G,
+                                                            scale);
+  else
+    defacto_update_kernel<ST, 1><<<grid, kThreads, 0, st>>>(s.d, s.ld, static_cast<ST *>(X), static_cast<ST *>(Xt), G,
+                                                            scale);
+  return hip_rc(hipGetLastError());
+}
+
+int launch_defacto_update(const Shape &s, void *X, void *Xt, float *G, float scale, void *stream) {
+  return s.bf16 ? launch_defacto_update_t<bf16_t>(s, X, Xt, G, scale, stream)
+                : launch_defacto_update_t<float>(s, X, Xt, G, scale, stream);
+}
 
 int launch_accumulate(const Shape &s, float *Gacc, const float *g, float scale, void *stream) {
   const bool vec = vec_ok(s, {}, {Gacc, g});

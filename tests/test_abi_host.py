@@ -122,6 +122,33 @@ def test_phase_length_of_theorem_3():
     assert ei.value.status == D.DETAG_EINVAL
 
 
+def test_consensus_factors_on_the_host():
+    """The library's average-consensus factors (built without a GPU) against the oracle's construction and
+    against Lemma 1 itself: same matrices, product 11^T/n, graph sparsity, R = 2 * eccentricity of the root."""
+    from oracle import consensus as OC
+    cases = [(D.Topology.ring(), 16, gen.edges_ring(16), 0), (D.Topology.torus(4, 8), 32, gen.edges_torus(4, 8), 5),
+             (D.Topology.from_edges(gen.edges_path(9), D.DETAG_W_METROPOLIS), 9, gen.edges_path(9), 4)]
+    for topo, n, edges, root in cases:
+        ctx = D.detag_create(topo, n, 8)
+        f = D.Factors(ctx, root)
+        ref = OC.gather_propagate_factors(n, edges, root)
+        assert f.R == len(ref)
+        P = np.eye(n)
+        for r in range(f.R):
+            A = f.dense(r)
+            assert np.array_equal(A, ref[r])
+            P = A @ P
+        assert np.allclose(P, 1.0 / n, rtol=0, atol=1e-15)
+        f.close()
+    ctx = D.detag_create(D.Topology.ring(), 8, 8)
+    with pytest.raises(D.DetagError):
+        D.Factors(ctx, 8)
+    with pytest.raises(D.DetagError):
+        D.Factors(ctx, -1)
+    one = D.Factors(D.detag_create(D.Topology.ring(), 1, 8), 0)
+    assert one.R == 0
+
+
 def test_asymmetric_W_is_accepted_without_eta():
     P = np.roll(np.eye(5), 1, axis=1)
     W = 0.5 * np.eye(5) + 0.5 * P

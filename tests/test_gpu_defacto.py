@@ -1,0 +1,91 @@
+"""DeFacto (Algorithm 1) and the exact average consensus of Lemma 1 on the
+device, against the oracle's dense construction."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_08085_amd as D
+from oracle import consensus as OC
+from oracle import objectives as OO
+from paper_2006_08085_amd import algorithms as ALG
+from tests.gpu_util import DEV, _built, padding_ok, to_dev, to_host  # noqa: F401
+from tests.util import TOL_BF16, TOL_F32, amax, rel_err
+from workloads import CONFIGS, generate as gen
+
+pytestmark = pytest.mark.gpu
+
+GRAPHS = [("ring16", lambda: D.Topology.ring(), 16, gen.edges_ring(16), 0),
+          ("torus8x8", lambda: D.Topology.torus(8, 8), 64, gen.edges_torus(8, 8), 9),
+          ("path9", lambda: D.Topology.from_edges(gen.edges_path(9), D.DETAG_W_METROPOLIS), 9, gen.edges_path(9), 4),
+          ("rr40", lambda: D.Topology.from_edges(gen.edges_random_regular(40, 4, seed=2), D.DETAG_W_METROPOLIS), 40,
+           gen.edges_random_regular(40, 4, seed=2), 7)]
+
+
+@pytest.mark.parametrize("name,topo,n,edges,root", GRAPHS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_factors_reach_the_exact_average(name, topo, n, edges, root, dtype):
+    """Every factor step against the oracle's dense product, and the end state against the worker mean."""
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    d, ld = 1029, 1032
+    ctx = D.detag_create(topo(), n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    f = D.Factors(ctx, root)
+    ref = OC.gather_propagate_factors(n, edges, root)
+    assert f.R == len(ref)
+    Z = gen.state(n, d, 1)
+    if bf:
+        Z = OO.round_bf16(Z)
+    S = n * amax(Z)                                       # the root holds the sum of all workers on the way
+    a, b = to_dev(Z, ld, tdt), to_dev(np.zeros((n, d)), ld, tdt)
+    Zr = Z.astype(np.float64)
+    for r in range(f.R):
+        f.apply(r, a, b)
+        a, b = b, a
+        Zr = ref[r] @ Zr
+        if not bf:                                        # (bf16 rounds every step's store; judged at the end)
+            assert rel_err(to_host(a, d), Zr, S, floor=1.0) < TOL_F32, r
+        assert padding_ok(a, d)
+    mean = np.tile(Z.astype(np.float64).mean(0), (n, 1))
+    assert np.allclose(Zr, mean, atol=1e-12)
+    # 2*depth roundings of values up to n times the entries, then divided back: normwise against the sum's scale
+    assert rel_err(to_host(a, d), mean, S, floor=1.0) < tol
+    with pytest.raises(D.DetagError):
+        f.apply(f.R, a, b)
+    with pytest.raises(D.DetagError):
+        f.apply(0, a, a)
+
+
+def test_defacto_run_matches_oracle():
+    """First workload's objective (least squares, n=8 ring, d=1024) under Algorithm 1: R = 8 factors, two gradient
+    queries per iteration, three rounds and part of a fourth."""
+    cfg = CONFIGS[1]
+    n, d, m = cfg.n, cfg.d, cfg.extra["m"]
+    A, b = gen.lstsq_problem(n, m, d, seed=cfg.seed, shift=cfg.extra["offset_shift"])
+    Ad, bd = torch.from_numpy(A).to(DEV), torch.from_numpy(b).to(DEV)
+    ctx = D.detag_create(D.Topology.ring(), n, d, d)
+    f = D.Factors(ctx, 0)
+    ref = OC.gather_propagate_factors(n, gen.edges_ring(n), 0)
+    assert f.R == len(ref) == 8
+    B, T, alpha = 2, 3 * 16 + 11, 0.02
+    Xd = D.new_matrix(n, d, d)
+    rounds = ALG.run_defacto(ctx, f, lambda t, q, X, g: ctx.grad_lstsq(X, Ad, bd, g), Xd, alpha, T, B=B)
+    Xr, rounds_ref = OC.defacto(lambda t, q, X: OO.grad_lstsq(X, A, b), np.zeros((n, d)), ref, alpha, T, B=B)
+    assert rounds == rounds_ref == 3
+    assert rel_err(to_host(Xd, d), Xr, amax(Xr, b), floor=1.0) < TOL_F32
+    # the loss at the worker mean has gone down
+    loss = lambda x: 0.5 * np.mean([np.sum((A[i].astype(np.float64) @ x - b[i]) ** 2) for i in range(n)])
+    assert loss(to_host(Xd, d).mean(0)) < 0.8 * loss(np.zeros(d))
+
+
+@pytest.mark.parametrize("separate", [True, False])
+def test_defacto_update(separate):
+    n, d, ld = 6, 700, 704
+    ctx = D.detag_create(D.Topology.ring(), n, d, ld)
+    Xt, G = gen.state(n, d, 1), gen.state(n, d, 2)
+    Xtd, Gd = to_dev(Xt, ld), to_dev(G, ld)
+    Xd = to_dev(np.zeros((n, d)), ld) if separate else Xtd
+    ctx.defacto_update(Xd, Xtd, Gd, 0.125)
+    want = Xt.astype(np.float64) - 0.125 * G
+    assert rel_err(to_host(Xd, d), want, amax(Xt, G)) < TOL_F32
+    assert np.array_equal(to_host(Xtd, d), to_host(Xd, d)) and np.all(to_host(Gd, d) == 0.0)
+    assert padding_ok(Xd, d) and padding_ok(Xtd, d) and padding_ok(Gd, d)
