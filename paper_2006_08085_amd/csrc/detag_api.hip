@@ -473,40 +473,49 @@ detag_status detag_phase_end(detag_ctx *ctx, void *X_dev, void *Xt_dev, void *Y_
   return rc ? hip_fail(ctx, "phase end", rc) : DETAG_OK;
 }
 
+namespace {
+detag_status factors_create_impl(detag_ctx *ctx, int32_t root, detag_factors *f) {
+  f->ctx = ctx;
+  std::string err;
+  if (!build_consensus_factors(ctx->W, root, f->host, err)) return set_err(ctx, DETAG_EINVAL, err);
+  int64_t nnz = 0;
+  for (auto &h : f->host) f->offs.push_back(nnz), nnz += int64_t(h.colidx.size());
+  if (!ctx->has_device || f->host.empty()) return DETAG_OK;
+  std::vector<int32_t> rp, ci;
+  std::vector<float> va;
+  for (auto &h : f->host) {
+    rp.insert(rp.end(), h.rowptr.begin(), h.rowptr.end());
+    ci.insert(ci.end(), h.colidx.begin(), h.colidx.end());
+    for (double v : h.vals) va.push_back(float(v));
+  }
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&f->d_rowptr), rp.size() * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_colidx), ci.size() * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_vals), va.size() * sizeof(float));
+  if (e == hipSuccess) e = hipMemcpy(f->d_rowptr, rp.data(), rp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(f->d_colidx, ci.data(), ci.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(f->d_vals, va.data(), va.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return hip_fail(ctx, "factor upload", int(e));
+  }
+  return DETAG_OK;
+}
+}  // namespace
+
 detag_status detag_factors_create(detag_ctx *ctx, int32_t root, detag_factors **out) {
   if (out) *out = nullptr;
   if (!ctx || !out) return set_err(ctx, DETAG_EINVAL, "ctx or out is NULL");
   auto *f = new (std::nothrow) detag_factors;
   if (!f) return set_err(ctx, DETAG_ENOMEM, "out of host memory");
-  f->ctx = ctx;
-  std::string err;
-  if (!build_consensus_factors(ctx->W, root, f->host, err)) {
-    delete f;
-    return set_err(ctx, DETAG_EINVAL, err);
+  detag_status st;
+  try {
+    st = factors_create_impl(ctx, root, f);
+  } catch (const std::bad_alloc &) {
+    st = set_err(ctx, DETAG_ENOMEM, "out of host memory");
   }
-  const int n = ctx->W.n, R = int(f->host.size());
-  int64_t nnz = 0;
-  for (auto &h : f->host) f->offs.push_back(nnz), nnz += int64_t(h.colidx.size());
-  if (ctx->has_device && R > 0) {
-    std::vector<int32_t> rp, ci;
-    std::vector<float> va;
-    for (auto &h : f->host) {
-      rp.insert(rp.end(), h.rowptr.begin(), h.rowptr.end());
-      ci.insert(ci.end(), h.colidx.begin(), h.colidx.end());
-      for (double v : h.vals) va.push_back(float(v));
-    }
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&f->d_rowptr), rp.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_colidx), ci.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&f->d_vals), va.size() * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(f->d_rowptr, rp.data(), rp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(f->d_colidx, ci.data(), ci.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(f->d_vals, va.data(), va.size() * sizeof(float), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-      (void)hipGetLastError();
-      detag_factors_destroy(f);
-      return hip_fail(ctx, "factor upload", int(e));
-    }
-    (void)n;
+  if (st != DETAG_OK) {
+    detag_factors_destroy(f);
+    return st;
   }
   *out = f;
   return DETAG_OK;
