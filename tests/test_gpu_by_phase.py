@@ -168,3 +168,52 @@ def test_recorded_graph_of_two_phases_replays_like_eager(R):
     assert bg.k == be.k == 8
     assert np.array_equal(Xg.cpu().numpy(), Xe.cpu().numpy())
     assert np.array_equal(bg.Y.cpu().numpy(), be.Y.cpu().numpy())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_odd_pitch_takes_the_scalar_paths(dtype):
+    """Pitch 517: no row is 16-byte (or, for bf16, 8-byte) aligned, so every streaming kernel runs its
+    one-element-per-lane form: the gossip step, the accumulation, the phase end, the per-round phase (with its
+    widening and narrowing copies for bf16), a consensus factor and the DeFacto update."""
+    from oracle import consensus as OC
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    n, d, ld, eta, alpha, K = 6, 515, 517, 0.3, 0.1, 3
+    ctx, W = make_ctx("ring", n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    rnd = (lambda a: OO.round_bf16(a)) if bf else (lambda a: a)
+    X, Y = rnd(gen.state(n, d, 1)), rnd(gen.state(n, d, 2))
+    Gk, Gm = gen.state(n, d, 3), gen.state(n, d, 4)
+    # one gossip step
+    Xd, Yd, Od = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(np.zeros((n, d)), ld, tdt)
+    ctx.gossip_round(Xd, Yd, Od, eta)
+    want = (1 + eta) * (W.T @ X.astype(np.float64)) - eta * Y.astype(np.float64)
+    assert rel_err(to_host(Od, d), want, amax(X, Y)) < tol and padding_ok(Od, d)
+    # accumulation and phase end
+    Gkd, Gmd = to_dev(Gk, ld), to_dev(Gm, ld)
+    ctx.accumulate(Gkd, Gmd, 0.5)
+    Gk2 = Gk.astype(np.float64) + 0.5 * Gm
+    assert rel_err(to_host(Gkd, d), Gk2, amax(Gk, Gm)) < TOL_F32 and padding_ok(Gkd, d)
+    ctx.phase_end(Od, Xd, Yd, Gkd, Gmd, alpha)
+    assert rel_err(to_host(Od, d), X.astype(np.float64) - alpha * Y, amax(X, Y)) < tol
+    assert rel_err(to_host(Yd, d), Y.astype(np.float64) + to_host(Gkd, d) - Gm, amax(Y, Gk2, Gm)) < tol
+    assert all(padding_ok(t, d) for t in (Od, Xd, Yd, Gmd))
+    # the per-round phase
+    ctx.set_path(D.DETAG_PATH_PER_ROUND)
+    Xd, Yd = to_dev(X, ld, tdt), to_dev(Y, ld, tdt)
+    ctx.step(Xd, Yd, to_dev(Gk, ld), to_dev(Gm, ld), alpha, K, eta)
+    Xr, Yr = OG.detag_step(X, Y, Gk, Gm, W, alpha, K, eta)
+    S = amax(X, Y, Gk, Gm)
+    assert rel_err(to_host(Xd, d), Xr, S) < tol and rel_err(to_host(Yd, d), Yr, S) < tol
+    assert padding_ok(Xd, d) and padding_ok(Yd, d)
+    # a consensus factor and the DeFacto update
+    f = D.Factors(ctx, 2)
+    ref = OC.gather_propagate_factors(n, gen.edges_ring(n), 2)
+    Zd, Od = to_dev(X, ld, tdt), to_dev(np.zeros((n, d)), ld, tdt)
+    f.apply(0, Zd, Od)
+    assert rel_err(to_host(Od, d), ref[0] @ X.astype(np.float64), 2 * amax(X)) < tol and padding_ok(Od, d)
+    Gd = to_dev(Gk, ld)
+    held = to_host(Od, d)
+    ctx.defacto_update(Zd, Od, Gd, 0.25)
+    assert rel_err(to_host(Zd, d), held - 0.25 * Gk, amax(held, Gk)) < tol
+    assert np.array_equal(to_host(Od, d), to_host(Zd, d)) and np.all(to_host(Gd, d) == 0.0)
+    assert padding_ok(Zd, d) and padding_ok(Gd, d)
