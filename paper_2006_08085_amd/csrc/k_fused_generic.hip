@@ -12,8 +12,10 @@
 // consecutive words, free of bank conflicts.  One round = read the neighbours
 // from LDS, barrier, write the new values back, barrier.  HBM sees the state
 // once per phase (the ATC phase reads Y twice: 18 B instead of 16 B per element
-// with bf16 state); the kernel is bound by LDS bandwidth and VALU issue,
-// (deg+1) LDS words and about 3*deg VALU operations per output per round.
+// with bf16 state); the rounds run at the LDS bandwidth, (deg+1) LDS words per
+// output per round.  The kernel is kept within 64 VGPRs so that two blocks
+// share a compute unit (2 x 64 KiB of LDS): one block's loads and stores then
+// run under the other's rounds.
 //
 // Paper: Algorithm 3 (accelerated gossip) and Algorithm 2 / the matrix form in
 // the proof of Theorem 3 (phase update).
@@ -45,7 +47,14 @@ struct RowTab {
 // One round for this lane's rows: v <- cm * sum_k W_ji (lds[j] - z) + eta * v;  z <- z + v;  then publish z.
 template <int DEG, bool UNI, bool FIRST>
 __device__ __forceinline__ void round_step(float (&z)[kRpt], float (&v)[kRpt], const char *lds_b, float *lds, int w,
-                                           int lane, const RowTab<DEG, UNI> (&tab)[kRpt], float cm, float eta) {
+                                           int lane, RowTab<DEG, UNI> (&tab)[kRpt], float cm, float eta) {
+  // The packed offset words are made opaque once per round: otherwise their 16-bit halves are unpacked ahead
+  // of the round loop into 4*DEG*... scalar registers of their own, which do not fit beside the table at two
+  // blocks per compute unit and end up spilled.
+#pragma unroll
+  for (int r = 0; r < kRpt; ++r)
+#pragma unroll
+    for (int q = 0; q < DEG / 2; ++q) asm volatile("" : "+s"(tab[r].w[q]));
   const uint32_t lane4 = uint32_t(lane) * 4u;
   auto nb = [&](int r, int k) { return *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4)); };
 #pragma unroll
@@ -80,7 +89,7 @@ __device__ __forceinline__ void round_step(float (&z)[kRpt], float (&v)[kRpt], c
 // K >= 1 rounds from z_{-1} = z_0 = z.  Result in z; v is scratch.
 template <int DEG, bool UNI>
 __device__ __forceinline__ void gossip(float (&z)[kRpt], float (&v)[kRpt], float *lds, int w, int lane,
-                                       const RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
+                                       RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
   const float cm = 1.f + eta;
   const char *lds_b = reinterpret_cast<const char *>(lds);
 #pragma unroll
@@ -98,11 +107,11 @@ __device__ __forceinline__ rsrc_t win(const E *base, int64_t tile, int64_t ld, i
 
 // mode 0: Z <- M(Z) on X.  mode 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
 // mode 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
-template <typename ST, int DEG, bool UNI>
-__global__ __launch_bounds__(kThreads) void fused_generic_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
-                                                                 const float *__restrict__ Go, int n, int64_t d,
-                                                                 int64_t ld, const uint32_t *__restrict__ table,
-                                                                 float eta, float alpha, int K, int mode) {
+template <typename ST, int DEG, bool UNI, int MODE>
+__global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
+                                                                    const float *__restrict__ Go, int n, int64_t d,
+                                                                    int64_t ld, const uint32_t *__restrict__ table,
+                                                                    float eta, float alpha, int K) {
   extern __shared__ float lds[];  // 256 x 64
   // the wavefront index is uniform: say so, or the row indices and with them every
   // table access are treated as per-lane values
@@ -118,46 +127,88 @@ __global__ __launch_bounds__(kThreads) void fused_generic_kernel(ST *X, ST *Y, c
     for (int q = 0; q < TS; ++q) tab[r].w[q] = table[(w * kRpt + r) * TS + q];
   float cur[kRpt], prev[kRpt];
   auto row = [&](int r) { return w + kWaves * r; };
-  if (mode == 0) {
+  // Loads and stores go four rows at a time with the scheduler fenced in between: left alone, the compiler
+  // issues all 16 rows' loads of every array at once, and the registers they hold decide how many blocks
+  // fit on a compute unit.  Two blocks per unit is what lets one block's memory phases run under the
+  // other's rounds.
+  constexpr int kBatch = 4;
+  if constexpr (MODE == 0) {
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+#pragma unroll
+      for (int r = r0; r < r0 + kBatch; ++r) cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
     for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
-  } else if (mode == 1) {
+  } else if constexpr (MODE == 1) {
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r)
-      cur[r] = fmaf(-alpha, buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so),
-                    buf_load<ST>(win(X, tile, ld, row(r), n, valid), so));
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+      float x[kBatch], y[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        x[q] = buf_load<ST>(win(X, tile, ld, row(r0 + q), n, valid), so);
+        y[q] = buf_load<ST>(win(Y, tile, ld, row(r0 + q), n, valid), so);
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) cur[r0 + q] = fmaf(-alpha, y[q], x[q]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
     for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r)
-      cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so) +
-               buf_load<float>(win(Gn, tile, ld, row(r), n, valid), fo) -
-               buf_load<float>(win(Go, tile, ld, row(r), n, valid), fo);
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+      float y[kBatch], gn[kBatch], go[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        y[q] = buf_load<ST>(win(Y, tile, ld, row(r0 + q), n, valid), so);
+        gn[q] = buf_load<float>(win(Gn, tile, ld, row(r0 + q), n, valid), fo);
+        go[q] = buf_load<float>(win(Go, tile, ld, row(r0 + q), n, valid), fo);
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) cur[r0 + q] = y[q] + gn[q] - go[q];
+      __builtin_amdgcn_sched_barrier(0);
+    }
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
     for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so, cur[r]);
   } else {
     // M(Y) first: both outputs need it
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so);
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+#pragma unroll
+      for (int r = r0; r < r0 + kBatch; ++r) cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
     float v[kRpt];
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) {
-      v[r] = cur[r];
-      cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+#pragma unroll
+      for (int r = r0; r < r0 + kBatch; ++r) {
+        v[r] = cur[r];
+        cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) {
-      buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, fmaf(-alpha, v[r], cur[r]));
-      buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so,
-                    v[r] + buf_load<float>(win(Gn, tile, ld, row(r), n, valid), fo) -
-                        buf_load<float>(win(Go, tile, ld, row(r), n, valid), fo));
+    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+      float gn[kBatch], go[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        gn[q] = buf_load<float>(win(Gn, tile, ld, row(r0 + q), n, valid), fo);
+        go[q] = buf_load<float>(win(Go, tile, ld, row(r0 + q), n, valid), fo);
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        buf_store<ST>(win(X, tile, ld, row(r0 + q), n, valid), so, fmaf(-alpha, v[r0 + q], cur[r0 + q]));
+        buf_store<ST>(win(Y, tile, ld, row(r0 + q), n, valid), so, v[r0 + q] + gn[q] - go[q]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -167,8 +218,24 @@ int launch_k(const Shape &s, const uint32_t *table, int mode, void *X, void *Y, 
              float alpha, int K, float eta, void *stream) {
   const dim3 grid(ceil_div_i64(s.d, kCols));
   const size_t lds_bytes = size_t(kRowsMax) * kCols * sizeof(float);  // 64 KiB
-  fused_generic_kernel<ST, DEG, UNI><<<grid, kThreads, lds_bytes, static_cast<hipStream_t>(stream)>>>(
-      static_cast<ST *>(X), static_cast<ST *>(Y), Gn, Go, s.n, s.d, s.ld, table, eta, alpha, K, mode);
+  auto st = static_cast<hipStream_t>(stream);
+  ST *x = static_cast<ST *>(X), *y = static_cast<ST *>(Y);
+  switch (mode) {
+    case 0:
+      fused_generic_kernel<ST, DEG, UNI, 0><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
+                                                                              alpha, K);
+      break;
+    case 1:
+      fused_generic_kernel<ST, DEG, UNI, 1><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
+                                                                              alpha, K);
+      break;
+    case 2:
+      fused_generic_kernel<ST, DEG, UNI, 2><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
+                                                                              alpha, K);
+      break;
+    default:
+      return hip_rc(hipErrorInvalidValue);
+  }
   return hip_rc(hipGetLastError());
 }
 
