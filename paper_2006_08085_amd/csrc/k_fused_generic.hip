@@ -4,9 +4,9 @@
 //
 // A block of 16 wavefronts owns 64 columns and all n rows of them.  Wavefront w
 // owns the rows w, w+16, w+32, ... (16 of them); lane l owns column l.  Each lane
-// keeps z_r and z_{r-1} of its own 16 rows in registers; z_r of ALL rows also
-// sits in LDS (256 x 64 fp32),
-// where the neighbours of a row are read.  Row indices are wavefront-uniform:
+// keeps z_r and the velocity z_r - z_{r-1} of its own 16 rows in registers; z_r
+// of ALL rows also sits in LDS (256 x 64 fp32), where the neighbours of a row
+// are read.  Row indices are wavefront-uniform:
 // the neighbour list of a row is a handful of scalars (16-bit LDS offsets packed
 // in pairs, the weights), read once per kernel, and every LDS access is 64
 // consecutive words, free of bank conflicts.  One round = read the neighbours
