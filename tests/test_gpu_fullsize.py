@@ -87,3 +87,76 @@ def test_config4_full_size_sampled_columns():
     # a property that holds at any size (proof of Theorem 3): mean(Y) - mean(last gradient) never changes
     offset = (ctx.mean(Y) - ctx.mean(Gb))[:d]
     assert (offset - offset0).abs().max().item() < 2e-5
+
+
+def test_config4_full_size_single_kernel_step():
+    """The entry point bench.py times by default (gradient query + phase in one kernel) at full size: one step
+    from a mid-run state against the oracle on sampled columns, and bit for bit against the two separate
+    kernels on the same inputs."""
+    cfg = CONFIGS[4]
+    n, d, K, alpha, sigma, seed = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.sigma, cfg.seed
+    ld = D.padded_ld(d)
+    ctx = D.detag_create(D.Topology.torus(8, 8), n, d, ld)
+    W = ctx.dense_W()
+    OT.check_gossip_matrix(W, gen.edges_torus(8, 8))
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    dev = torch.device(DEV)
+    b = gen.device_normal(n, d, ld, seed, 1, dev, std=cfg.extra["b_std"])
+    h = gen.device_log_uniform(d, ld, seed, 2, dev, cfg.extra["h_lo"], cfg.extra["h_hi"])
+    X = gen.device_normal(n, d, ld, seed, 3, dev)
+    Y = gen.device_normal(n, d, ld, seed, 4, dev)
+    G = gen.device_normal(n, d, ld, seed, 5, dev)              # holds G_old on entry, this step's gradient on exit
+    cols = _sample_columns(d, np.random.default_rng(1))
+    idx = torch.from_numpy(cols).to(dev)
+    take = lambda t: t[:, idx].double().cpu().numpy()
+    Xs, Ys, Gos, bs = take(X), take(Y), take(G), take(b)
+    hs = h[idx].double().cpu().numpy()
+    X2, Y2, Gold2 = X.clone(), Y.clone(), G.clone()
+    step = 7
+    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma=sigma, seed=seed, step=step)
+    Gns = OO.grad_quadratic_diag(Xs, hs, bs, ON.normal_noise(seed, step, n, cols), sigma)
+    Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
+    S = amax(Xs, Ys, Gns, Gos)
+    assert rel_err(take(G), Gns, S) < TOL_F32
+    assert rel_err(take(X), Xr, S) < TOL_F32
+    assert rel_err(take(Y), Yr, S) < TOL_F32
+    Gnew2 = D.new_matrix(n, d, ld, device=dev)
+    ctx.grad_quadratic_diag(X2, h, b, Gnew2, sigma=sigma, seed=seed, step=step)
+    ctx.step(X2, Y2, Gnew2, Gold2, alpha, K)
+    torch.cuda.synchronize()
+    assert torch.equal(X, X2) and torch.equal(Y, Y2) and torch.equal(G, Gnew2)
+
+
+def test_config5_full_size_sampled_columns():
+    """n=256, the library's own random 4-regular graph (seeded) with Metropolis weights, d=1,048,576, bf16 X and
+    Y, K=16: one phase from a mid-run state in the configuration bench.py --config 5 times.  The graph reaches
+    the oracle as data (the library's CSR), re-validated there."""
+    cfg = CONFIGS[5]
+    n, d, K, alpha, seed = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.seed
+    ld = D.padded_ld(d)
+    ctx = D.detag_create(D.Topology.random_regular(cfg.degree, seed), n, d, ld, D.DETAG_BF16)
+    assert ctx.has_fused()
+    W = ctx.dense_W()
+    OT.check_gossip_matrix(W)
+    off = W - np.diag(np.diag(W))
+    assert np.array_equal(W, W.T) and np.all((off != 0).sum(1) == cfg.degree) and np.allclose(off[off != 0], 0.2)
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    assert ctx.spectrum()["eta"] == pytest.approx(eta, abs=1e-12)
+    dev = torch.device(DEV)
+    X = gen.device_normal(n, d, ld, seed, 3, dev, dtype=torch.bfloat16)
+    Y = gen.device_normal(n, d, ld, seed, 4, dev, dtype=torch.bfloat16)
+    Gn = gen.device_normal(n, d, ld, seed, 5, dev)
+    Go = gen.device_normal(n, d, ld, seed, 6, dev)
+    cols = np.unique(np.concatenate([np.arange(0, 130), np.arange(d - 70, d),
+                                     np.random.default_rng(2).integers(0, d, 600)]))
+    idx = torch.from_numpy(cols).to(dev)
+    take = lambda t: t[:, idx].double().cpu().numpy()
+    Xs, Ys, Gns, Gos = take(X), take(Y), take(Gn), take(Go)
+    ctx.step(X, Y, Gn, Go, alpha, K)
+    Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
+    S = amax(Xs, Ys, Gns, Gos)
+    from tests.util import TOL_BF16
+    assert rel_err(take(X), Xr, S) < TOL_BF16
+    assert rel_err(take(Y), Yr, S) < TOL_BF16
+    # fp32 on chip, rounded once: within half a bf16 ulp of the oracle wherever the value is not tiny
+    assert rel_err(take(X), Xr) < 2.0 ** -8 and rel_err(take(Y), Yr) < 2.0 ** -8
