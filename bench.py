@@ -87,7 +87,7 @@ def main():
                          "traffic, for scaling profiler byte counters); untimed")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no cross-GPU code exists); use --gpus 1", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only (it has no cross-GPU code); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -46,7 +46,7 @@ typedef enum {
   DETAG_EINVAL = 1,                /* bad argument (null, size, range, alignment) */
   DETAG_ENOT_DOUBLY_STOCHASTIC = 2,/* a row or column of W does not sum to 1, or a weight is negative */
   DETAG_EDISCONNECTED = 3,         /* the support graph of W is not connected (lambda = 1) */
-  DETAG_EUNSUPPORTED = 4,          /* valid request this build has no kernel for */
+  DETAG_EUNSUPPORTED = 4,          /* valid request the library has no kernel for */
   DETAG_ENOMEM = 5,                /* host or device allocation failed */
   DETAG_EHIP = 6                   /* HIP runtime error, or no GPU present */
 } detag_status;

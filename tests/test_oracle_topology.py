@@ -76,7 +76,7 @@ def test_printed_ring16_gaps(golden_dir):
     """The captions of the second experiment print 1-lambda for four kappas.
     Their ratios must equal kappa (what slack() does); the absolute value at
     kappa=1 is reproduced, to the one digit printed, by a ring with neighbour
-    weight 1/4 (self 1/2) — and not by 1/3, which this build's configs use."""
+    weight 1/4 (self 1/2) — and not by 1/3, which the workloads here use."""
     rows = [ln.split() for ln in open(os.path.join(golden_dir, "paper_ring16_spectral_gaps.txt"))
             if ln.strip() and not ln.startswith("#")]
     printed = {float(k): float(g) for k, g in rows}
