@@ -11,6 +11,15 @@ namespace fused {
 
 constexpr int kThreads = 256;
 
+// Workgroups are handed to the eight XCDs (each with its own L2) round-robin by their index.  Mapping index b
+// to column tile (b % 8) * (tiles / 8) + b / 8 gives every XCD one contiguous eighth of the columns instead of
+// every eighth tile, so the lines one L2 holds are neighbours in memory.  The tiles past a multiple of eight
+// keep their own index.
+__device__ __forceinline__ int64_t xcd_tile(uint32_t b, uint32_t tiles) {
+  const uint32_t per = tiles / 8u;
+  return b < per * 8u ? int64_t(b % 8u) * per + b / 8u : int64_t(b);
+}
+
 template <int N>
 struct Ring {
   static constexpr int n = N, deg = 2;

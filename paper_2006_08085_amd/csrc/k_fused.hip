@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_st
     float alpha, int K) {
   constexpr int N = T::n;
   constexpr int D = kRowsAhead < N ? kRowsAhead : N;
-  const int64_t tile = int64_t(blockIdx.x) * kThreads;
+  const int64_t tile = xcd_tile(blockIdx.x, gridDim.x) * kThreads;
   const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
   const uint32_t so = threadIdx.x * uint32_t(sizeof(ST));  // lane byte offset in a state row
   const uint32_t go4 = threadIdx.x * 4u;                   // ... in an fp32 row

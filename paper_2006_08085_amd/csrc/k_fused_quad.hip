@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadr
   constexpr int N = T::n;
   static_assert(N % 4 == 0, "rows are processed in groups of four");
   constexpr int D = kRowsAhead < N ? kRowsAhead : N;
-  const int64_t tile = int64_t(blockIdx.x) * kThreads;
+  const int64_t tile = xcd_tile(blockIdx.x, gridDim.x) * kThreads;
   const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
   const uint32_t so = threadIdx.x * uint32_t(sizeof(ST)), fo = threadIdx.x * 4u;
   const unsigned j = threadIdx.x & 3u;
