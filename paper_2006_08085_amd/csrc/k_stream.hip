@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d
   }
 }
 
-// mode 0: Y += Gn - Go.   mode 1: X -= alpha*Y (Y before the update); Y += Gn - Go.   mode 2: dst(Y) = src(X) copy.
+// mode 0: Y += Gn - Go.   mode 1: X -= alpha*Y (Y before the update); Y += Gn - Go.
 template <typename ST, int VEC, int MODE>
 __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_t ld, ST *X, ST *Y,
                                                                const float *__restrict__ Gn,
@@ -114,26 +114,20 @@ __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_
   if (c0 >= d) return;
   const int valid = int(d - c0 < VEC ? d - c0 : VEC);
   const int64_t off = int64_t(blockIdx.y) * ld + c0;
-  if constexpr (MODE == 2) {
+  float y[VEC], gn[VEC], go[VEC];
+  load_vec<ST, VEC>(Y + off, valid, y);
+  load_vec<float, VEC>(Gn + off, valid, gn);
+  load_vec<float, VEC>(Go + off, valid, go);
+  if constexpr (MODE == 1) {
     float x[VEC];
     load_vec<ST, VEC>(X + off, valid, x);
-    store_vec<ST, VEC>(Y + off, valid, x);
-  } else {
-    float y[VEC], gn[VEC], go[VEC];
-    load_vec<ST, VEC>(Y + off, valid, y);
-    load_vec<float, VEC>(Gn + off, valid, gn);
-    load_vec<float, VEC>(Go + off, valid, go);
-    if constexpr (MODE == 1) {
-      float x[VEC];
-      load_vec<ST, VEC>(X + off, valid, x);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) x[e] = fmaf(-alpha, y[e], x[e]);
-      store_vec<ST, VEC>(X + off, valid, x);
-    }
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) y[e] = y[e] + gn[e] - go[e];
-    store_vec<ST, VEC>(Y + off, valid, y);
+    for (int e = 0; e < VEC; ++e) x[e] = fmaf(-alpha, y[e], x[e]);
+    store_vec<ST, VEC>(X + off, valid, x);
   }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) y[e] = y[e] + gn[e] - go[e];
+  store_vec<ST, VEC>(Y + off, valid, y);
 }
 
 // out[i,:] = sum_k vals[k] * cur[col[k],:] for a general sparse matrix (rows need not sum to one, may be empty):
@@ -413,8 +407,7 @@ int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const
 }
 
 int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream) {
-  return s.bf16 ? launch_elementwise_t<bf16_t, 2>(s, const_cast<void *>(src), dst, nullptr, nullptr, 0.f, stream)
-                : launch_elementwise_t<float, 2>(s, const_cast<void *>(src), dst, nullptr, nullptr, 0.f, stream);
+  return s.bf16 ? launch_convert_t<bf16_t, bf16_t>(s, src, dst, stream) : launch_convert_t<float, float>(s, src, dst, stream);
 }
 
 }  // namespace detag
