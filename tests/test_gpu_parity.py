@@ -367,13 +367,16 @@ def test_wide_rows_fall_back_to_the_per_round_path():
     assert rel_err(to_host(Zd, d), OG.accelerated_gossip(Z, W, K, eta_for(W)), amax(Z)) < TOL_F32
 
 
-@pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (61, "irregular"), (100, "irregular"), (130, "rr"), (256, "rr")])
+@pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (61, "irregular"), (100, "irregular"), (130, "rr"), (256, "rr"),
+                                     (1, "ring"), (2, "ring"), (3, "ring"), (17, "ring")])   # degenerate and odd rings
 @pytest.mark.parametrize("K", [1, 2, 5, 16])
 def test_generic_fused_gossip_and_step(n, graph, K):
     d, ld = 150, 160               # two full 64-column tiles and a ragged one
     if graph == "asym":
         W = 0.5 * np.eye(n) + 0.5 * np.roll(np.eye(n), 1, axis=1)
         topo = D.Topology.from_dense(W)
+    elif graph == "ring":          # n = 1: W = [1]; n = 2: one edge; sizes the register-resident kernels do not cover
+        topo, W = D.Topology.ring(), OT.mixing_matrix(n, gen.edges_ring(n))
     else:
         e = gen.edges_random_regular(n, 4, seed=n) if graph == "rr" else _irregular_edges(n, seed=n)
         topo, W = D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), OT.mixing_matrix(n, e, "metropolis")
