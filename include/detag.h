@@ -248,6 +248,14 @@ detag_status detag_factors_get_csr(const detag_factors *f, int32_t r, int64_t *n
 detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t r, const void *Zin_dev,
                                 void *Zout_dev, void *stream);
 /*
+ * All R factors in order, in place: Z <- A_{R-1} ... A_0 Z, after which every worker's row is the column mean
+ * (the R communication iterations of a round of Algorithm 1 as one call).  With up to 256 workers and at most
+ * 8 terms per factor row the whole sequence runs on chip and Z crosses memory once; otherwise (or with
+ * DETAG_PATH_PER_ROUND) it is one launch per factor through a context-owned scratch matrix.
+ */
+detag_status detag_average_consensus(detag_ctx *ctx, const detag_factors *f, void *Z_dev, void *stream);
+
+/*
  * End of a round of Algorithm 1: X <- Xt - scale*G;  Xt <- X;  G <- 0,
  * with Xt the averaged model copy, G the gradient buffer and scale = alpha/R.
  * X_dev, Xt_dev: state type (X_dev may equal Xt_dev); G_dev: fp32.

@@ -172,12 +172,17 @@ def run_by_phase(ctx: Context, grad: Callable, X, alpha: float, T: int, R, eta=-
     return bp
 
 
-def run_defacto(ctx: Context, factors: Factors, grad: Callable, X, alpha: float, T: int, B: int = 1) -> int:
+def run_defacto(ctx: Context, factors: Factors, grad: Callable, X, alpha: float, T: int, B: int = 1,
+                granularity: str = "iteration") -> int:
     """T iterations of Algorithm 1 (DeFacto) in place on X.  A round is 2R iterations, R = factors.R: R
     iterations of B gradient queries each at the round-start model, added to the gradient buffer; R iterations
     that multiply the model copy by the factors of the exact average consensus, one per iteration; then
     x <- copy - alpha * g / R.  grad(t, q, X, g) as in ByPhase.  An unfinished round leaves X at the last round
-    end.  Returns the number of completed rounds."""
+    end.  granularity = "round" issues the R communication iterations of a round as one
+    detag_average_consensus call at the first of them (on chip for up to 256 workers).
+    Returns the number of completed rounds."""
+    if granularity not in ("iteration", "round"):
+        raise ValueError("granularity must be 'iteration' or 'round'")
     import torch
     n, d, ld, dev, R = ctx.n, ctx.d, ctx.ld, X.device, factors.R
     G = new_matrix(n, d, ld, device=dev)
@@ -190,6 +195,9 @@ def run_defacto(ctx: Context, factors: Factors, grad: Callable, X, alpha: float,
             for q in range(B):
                 grad(t, q, X, g)
                 ctx.accumulate(G, g, 1.0)
+        elif granularity == "round":
+            if r == R:
+                factors.average(xt[0])
         else:
             factors.apply(r - R, xt[0], xt[1])
             xt[0], xt[1] = xt[1], xt[0]

@@ -32,7 +32,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
            "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
-           "detag_factor_apply", "detag_defacto_update",
+           "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
            "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
     L.detag_factors_get_csr.restype = C.c_int
     L.detag_factor_apply.argtypes = [vp, vp, i32, vp, vp, vp]
     L.detag_factor_apply.restype = C.c_int
+    L.detag_average_consensus.argtypes = [vp, vp, vp, vp]
+    L.detag_average_consensus.restype = C.c_int
     L.detag_defacto_update.argtypes = [vp, vp, vp, vp, f64, vp]
     L.detag_defacto_update.restype = C.c_int
     L.detag_mean.argtypes = [vp, vp, vp, vp]
@@ -231,6 +233,12 @@ class Factors:
         c = self.ctx
         c._check(lib().detag_factor_apply(c._h, self._h, r, c._state(Z_in, "Z_in"), c._state(Z_out, "Z_out"),
                                           c._stream()))
+
+
+    def average(self, Z):
+        """Z <- A_{R-1} ... A_0 Z in place: every row becomes the column mean."""
+        c = self.ctx
+        c._check(lib().detag_average_consensus(c._h, self._h, c._state(Z, "Z"), c._stream()))
 
 
 class Context:
@@ -459,6 +467,7 @@ def detag_factors_destroy(f: Factors): f.close()
 def detag_factors_count(f: Factors): return f.R
 def detag_factors_get_csr(f: Factors, r): return f.dense(r)
 def detag_factor_apply(ctx: Context, f: Factors, r, Z_in, Z_out): f.apply(r, Z_in, Z_out)
+def detag_average_consensus(ctx: Context, f: Factors, Z): f.average(Z)
 def detag_defacto_update(ctx: Context, X, X_tilde, G, scale): ctx.defacto_update(X, X_tilde, G, scale)
 def detag_mean(ctx: Context, X, out=None): return ctx.mean(X, out)
 def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error(X, out)

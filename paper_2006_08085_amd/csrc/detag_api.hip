@@ -41,6 +41,8 @@ struct detag_factors {
   int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
   float *d_vals = nullptr;
   std::vector<int64_t> offs;
+  uint32_t *d_table = nullptr;  // table of the on-chip kernel; NULL if build_factor_table declined
+  int table_words = 0;
 };
 
 namespace {
@@ -494,6 +496,12 @@ detag_status factors_create_impl(detag_ctx *ctx, int32_t root, detag_factors *f)
   if (e == hipSuccess) e = hipMemcpy(f->d_rowptr, rp.data(), rp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(f->d_colidx, ci.data(), ci.size() * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(f->d_vals, va.data(), va.size() * sizeof(float), hipMemcpyHostToDevice);
+  std::vector<uint32_t> table;
+  if (e == hipSuccess && build_factor_table(ctx->W.n, f->host, table)) {
+    e = hipMalloc(reinterpret_cast<void **>(&f->d_table), table.size() * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemcpy(f->d_table, table.data(), table.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
+    f->table_words = int(table.size());
+  }
   if (e != hipSuccess) {
     (void)hipGetLastError();
     return hip_fail(ctx, "factor upload", int(e));
@@ -523,11 +531,12 @@ detag_status detag_factors_create(detag_ctx *ctx, int32_t root, detag_factors **
 
 void detag_factors_destroy(detag_factors *f) {
   if (!f) return;
-  if (f->d_rowptr || f->d_colidx || f->d_vals) {
+  if (f->d_rowptr || f->d_colidx || f->d_vals || f->d_table) {
     (void)hipDeviceSynchronize();
     (void)hipFree(f->d_rowptr);
     (void)hipFree(f->d_colidx);
     (void)hipFree(f->d_vals);
+    (void)hipFree(f->d_table);
   }
   delete f;
 }
@@ -564,6 +573,35 @@ detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t 
   a.vals = f->d_vals + f->offs[r];
   const int rc = launch_spmm(ctx->shape, a, Zin_dev, Zout_dev, stream);
   return rc ? hip_fail(ctx, "factor apply", rc) : DETAG_OK;
+}
+
+detag_status detag_average_consensus(detag_ctx *ctx, const detag_factors *f, void *Z_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (!f || f->ctx != ctx) return set_err(ctx, DETAG_EINVAL, "the factors were not built for this context");
+  if (detag_status st = check_state_ptr(ctx, Z_dev, "Z_dev")) return st;
+  const int R = int(f->host.size());
+  if (R == 0) return DETAG_OK;
+  if (f->d_table && ctx->path != DETAG_PATH_PER_ROUND) {
+    const int rc = launch_factor_sequence(ctx->shape, f->d_table, f->table_words, Z_dev, stream);
+    if (rc == 0) return DETAG_OK;
+    if (rc > 0) return hip_fail(ctx, "factor sequence", rc);
+    // rc < 0: does not fit the LDS of a block here; fall through to one launch per factor
+  }
+  // one launch per factor, between Z and a scratch matrix
+  if (detag_status st = need_scratch(ctx, 0, 1)) return st;
+  void *cur = Z_dev, *other = ctx->scratch[0];
+  for (int r = 0; r < R; ++r) {
+    DevCsr a;
+    a.rowptr = f->d_rowptr + int64_t(r) * (ctx->W.n + 1);
+    a.colidx = f->d_colidx + f->offs[r];
+    a.vals = f->d_vals + f->offs[r];
+    if (int rc = launch_spmm(ctx->shape, a, cur, other, stream)) return hip_fail(ctx, "factor apply", rc);
+    void *t = cur;
+    cur = other, other = t;
+  }
+  if (cur != Z_dev)
+    if (int rc = launch_copy_state(ctx->shape, cur, Z_dev, stream)) return hip_fail(ctx, "copy", rc);
+  return DETAG_OK;
 }
 
 detag_status detag_defacto_update(detag_ctx *ctx, void *X_dev, void *Xt_dev, float *G_dev, double scale, void *stream) {

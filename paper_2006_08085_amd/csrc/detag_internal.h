@@ -39,6 +39,12 @@ struct HostFactor {
 // Spanning-tree (gather, then propagate) factors on the undirected support of W, rooted at `root`.
 bool build_consensus_factors(const HostW &W, int root, std::vector<HostFactor> &out, std::string &err);
 
+// Device table of a factor sequence for the on-chip kernel: batches of four 4-word operations (header, two packed
+// 16-bit LDS byte offsets, two fp32 weights) covering the non-identity rows of every factor in an order the kernel
+// may execute batch by batch.  false if n > 256, a factor row has more than 8 terms, or the rows a step changes
+// read each other in a cycle.
+bool build_factor_table(int n, const std::vector<HostFactor> &factors, std::vector<uint32_t> &table);
+
 // Eigenvalues (ascending) of a dense symmetric matrix, cyclic Jacobi. a is n*n row-major, destroyed.
 void symmetric_eigenvalues(std::vector<double> &a, int n, std::vector<double> &ev);
 
@@ -75,6 +81,9 @@ struct Shape {
   bool bf16;  // storage of X/Y
 };
 
+// Z <- A_{R-1} ... A_0 Z on chip, in place (table from build_factor_table).  -1 if n rows of 64 columns do not
+// fit a block's LDS on this device.
+int launch_factor_sequence(const Shape &s, const uint32_t *table, int table_words, void *Z, void *stream);
 // out = A cur for a CSR matrix A whose rows need not sum to one (row i lists (j, A_ij)); out != cur.
 int launch_spmm(const Shape &s, const DevCsr &a, const void *cur, void *out, void *stream);
 // X = Xt - scale*G; Xt = X; G = 0   (X may be Xt)

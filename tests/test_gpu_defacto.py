@@ -55,7 +55,38 @@ def test_factors_reach_the_exact_average(name, topo, n, edges, root, dtype):
         f.apply(0, a, a)
 
 
-def test_defacto_run_matches_oracle():
+@pytest.mark.parametrize("name,topo,n,edges,root", GRAPHS + [
+    ("rr256", lambda: D.Topology.random_regular(4, 3), 256, None, 100),
+    ("star9", lambda: D.Topology.from_edges([(0, i) for i in range(1, 9)], D.DETAG_W_METROPOLIS), 9, None, 0),
+    ("star12", lambda: D.Topology.from_edges([(0, i) for i in range(1, 12)], D.DETAG_W_METROPOLIS), 12, None, 0)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_average_consensus_in_one_call(name, topo, n, edges, root, dtype):
+    """detag_average_consensus (the whole factor sequence on chip; for the 11-leaf star, whose root row has more
+    than 8 terms, and with the per-round path forced, one launch per factor) leaves the column mean in every row."""
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    d, ld = 150, 160
+    ctx = D.detag_create(topo(), n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    f = D.Factors(ctx, root)
+    Z = gen.state(n, d, 1)
+    if bf:
+        Z = OO.round_bf16(Z)
+    mean = np.tile(Z.astype(np.float64).mean(0), (n, 1))
+    S = n * amax(Z)
+    for path in (D.DETAG_PATH_AUTO, D.DETAG_PATH_PER_ROUND):
+        ctx.set_path(path)
+        Zd = to_dev(Z, ld, tdt)
+        f.average(Zd)
+        if bf and path == D.DETAG_PATH_AUTO and name != "star12":
+            # on chip the sums stay in fp32 and only the result is rounded
+            assert rel_err(to_host(Zd, d), mean, amax(Z)) < tol
+        else:
+            assert rel_err(to_host(Zd, d), mean, S, floor=1.0) < tol
+        assert padding_ok(Zd, d)
+
+
+@pytest.mark.parametrize("granularity", ["iteration", "round"])
+def test_defacto_run_matches_oracle(granularity):
     """First workload's objective (least squares, n=8 ring, d=1024) under Algorithm 1: R = 8 factors, two gradient
     queries per iteration, three rounds and part of a fourth."""
     cfg = CONFIGS[1]
@@ -68,7 +99,8 @@ def test_defacto_run_matches_oracle():
     assert f.R == len(ref) == 8
     B, T, alpha = 2, 3 * 16 + 11, 0.02
     Xd = D.new_matrix(n, d, d)
-    rounds = ALG.run_defacto(ctx, f, lambda t, q, X, g: ctx.grad_lstsq(X, Ad, bd, g), Xd, alpha, T, B=B)
+    rounds = ALG.run_defacto(ctx, f, lambda t, q, X, g: ctx.grad_lstsq(X, Ad, bd, g), Xd, alpha, T, B=B,
+                             granularity=granularity)
     Xr, rounds_ref = OC.defacto(lambda t, q, X: OO.grad_lstsq(X, A, b), np.zeros((n, d)), ref, alpha, T, B=B)
     assert rounds == rounds_ref == 3
     assert rel_err(to_host(Xd, d), Xr, amax(Xr, b), floor=1.0) < TOL_F32
