@@ -254,6 +254,17 @@ detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t 
  * DETAG_PATH_PER_ROUND) it is one launch per factor through a context-owned scratch matrix.
  */
 detag_status detag_average_consensus(detag_ctx *ctx, const detag_factors *f, void *Z_dev, void *stream);
+/*
+ * Host view of what the on-chip form of detag_average_consensus executes (for inspection and tests; lives until
+ * detag_factors_destroy): `*batches` batches of 4 operations of 8 words each,
+ *   { o0, o1, dst, keep, w0, w1, m0, m1 }:   acc = (previous acc & keep) + w0*(row[o0] & m0) + w1*(row[o1] & m1),
+ *                                            row[dst] = acc,
+ * o0, o1, dst = 256 * row index, w0, w1 fp32 bit patterns, keep/m0/m1 all ones or 0, the first operation of a batch
+ * starting from 0.  A batch reads all its operands before it writes any row and writes in operation order.  The
+ * batches in order give the same rows as the R factors in order.  `*batches` = 0 when the sequence is not run that
+ * way (more than 256 workers, a factor row with more than 8 terms, rows of a step that read each other in a cycle).
+ */
+detag_status detag_factors_get_program(const detag_factors *f, int64_t *batches, const uint32_t **words);
 
 /*
  * End of a round of Algorithm 1: X <- Xt - scale*G;  Xt <- X;  G <- 0,

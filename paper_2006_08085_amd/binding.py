@@ -32,6 +32,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
            "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
+           "detag_factors_get_program",
            "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
            "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
@@ -101,6 +102,8 @@ def lib() -> C.CDLL:
     L.detag_factors_get_csr.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.POINTER(i32)), C.POINTER(C.POINTER(i32)),
                                         C.POINTER(C.POINTER(f64))]
     L.detag_factors_get_csr.restype = C.c_int
+    L.detag_factors_get_program.argtypes = [vp, C.POINTER(i64), C.POINTER(C.POINTER(C.c_uint32))]
+    L.detag_factors_get_program.restype = C.c_int
     L.detag_factor_apply.argtypes = [vp, vp, i32, vp, vp, vp]
     L.detag_factor_apply.restype = C.c_int
     L.detag_average_consensus.argtypes = [vp, vp, vp, vp]
@@ -228,6 +231,15 @@ class Factors:
             for k in range(rp[i], rp[i + 1]):
                 A[i, ci[k]] = va[k]
         return A
+
+    def program(self) -> np.ndarray:
+        """The on-chip form of the sequence as a (batches, 4, 8) uint32 array (detag_factors_get_program); no
+        batches if the sequence is not run that way."""
+        nb, words = C.c_int64(), C.POINTER(C.c_uint32)()
+        self.ctx._check(lib().detag_factors_get_program(self._h, C.byref(nb), C.byref(words)))
+        if nb.value == 0:
+            return np.zeros((0, 4, 8), np.uint32)
+        return np.ctypeslib.as_array(words, shape=(nb.value, 4, 8)).copy()
 
     def apply(self, r: int, Z_in, Z_out):
         c = self.ctx
@@ -466,6 +478,7 @@ def detag_factors_create(ctx: Context, root=0): return Factors(ctx, root)
 def detag_factors_destroy(f: Factors): f.close()
 def detag_factors_count(f: Factors): return f.R
 def detag_factors_get_csr(f: Factors, r): return f.dense(r)
+def detag_factors_get_program(f: Factors): return f.program()
 def detag_factor_apply(ctx: Context, f: Factors, r, Z_in, Z_out): f.apply(r, Z_in, Z_out)
 def detag_average_consensus(ctx: Context, f: Factors, Z): f.average(Z)
 def detag_defacto_update(ctx: Context, X, X_tilde, G, scale): ctx.defacto_update(X, X_tilde, G, scale)

@@ -41,8 +41,8 @@ struct detag_factors {
   int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
   float *d_vals = nullptr;
   std::vector<int64_t> offs;
-  uint32_t *d_table = nullptr;  // table of the on-chip kernel; NULL if build_factor_table declined
-  int table_words = 0;
+  std::vector<uint32_t> table;  // program of the on-chip kernel; empty if build_factor_table declined
+  uint32_t *d_table = nullptr;
 };
 
 namespace {
@@ -482,6 +482,7 @@ detag_status factors_create_impl(detag_ctx *ctx, int32_t root, detag_factors *f)
   if (!build_consensus_factors(ctx->W, root, f->host, err)) return set_err(ctx, DETAG_EINVAL, err);
   int64_t nnz = 0;
   for (auto &h : f->host) f->offs.push_back(nnz), nnz += int64_t(h.colidx.size());
+  if (!build_factor_table(ctx->W.n, f->host, f->table)) f->table.clear();
   if (!ctx->has_device || f->host.empty()) return DETAG_OK;
   std::vector<int32_t> rp, ci;
   std::vector<float> va;
@@ -496,11 +497,10 @@ detag_status factors_create_impl(detag_ctx *ctx, int32_t root, detag_factors *f)
   if (e == hipSuccess) e = hipMemcpy(f->d_rowptr, rp.data(), rp.size() * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(f->d_colidx, ci.data(), ci.size() * sizeof(int32_t), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(f->d_vals, va.data(), va.size() * sizeof(float), hipMemcpyHostToDevice);
-  std::vector<uint32_t> table;
-  if (e == hipSuccess && build_factor_table(ctx->W.n, f->host, table)) {
-    e = hipMalloc(reinterpret_cast<void **>(&f->d_table), table.size() * sizeof(uint32_t));
-    if (e == hipSuccess) e = hipMemcpy(f->d_table, table.data(), table.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
-    f->table_words = int(table.size());
+  if (e == hipSuccess && !f->table.empty()) {
+    const size_t bytes = f->table.size() * sizeof(uint32_t);
+    e = hipMalloc(reinterpret_cast<void **>(&f->d_table), bytes);
+    if (e == hipSuccess) e = hipMemcpy(f->d_table, f->table.data(), bytes, hipMemcpyHostToDevice);
   }
   if (e != hipSuccess) {
     (void)hipGetLastError();
@@ -559,6 +559,13 @@ detag_status detag_factors_get_csr(const detag_factors *f, int32_t r, int64_t *n
   return DETAG_OK;
 }
 
+detag_status detag_factors_get_program(const detag_factors *f, int64_t *batches, const uint32_t **words) {
+  if (!f || !batches || !words) return DETAG_EINVAL;
+  *batches = int64_t(f->table.size() / 32);
+  *words = f->table.empty() ? nullptr : f->table.data();
+  return DETAG_OK;
+}
+
 detag_status detag_factor_apply(detag_ctx *ctx, const detag_factors *f, int32_t r, const void *Zin_dev,
                                 void *Zout_dev, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
@@ -582,7 +589,7 @@ detag_status detag_average_consensus(detag_ctx *ctx, const detag_factors *f, voi
   const int R = int(f->host.size());
   if (R == 0) return DETAG_OK;
   if (f->d_table && ctx->path != DETAG_PATH_PER_ROUND) {
-    const int rc = launch_factor_sequence(ctx->shape, f->d_table, f->table_words, Z_dev, stream);
+    const int rc = launch_factor_sequence(ctx->shape, f->d_table, int(f->table.size()), Z_dev, stream);
     if (rc == 0) return DETAG_OK;
     if (rc > 0) return hip_fail(ctx, "factor sequence", rc);
     // rc < 0: does not fit the LDS of a block here; fall through to one launch per factor

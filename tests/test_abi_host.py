@@ -149,6 +149,66 @@ def test_consensus_factors_on_the_host():
     assert one.R == 0
 
 
+def _run_program(prog, Z):
+    """The operations of detag_factors_get_program carried out as its description says, in fp64."""
+    tile = Z.copy()
+    f32 = lambda w: float(np.array([w], np.uint32).view(np.float32)[0])
+    for batch in prog:
+        reads = [(tile[int(op[0]) // 256].copy(), tile[int(op[1]) // 256].copy()) for op in batch]
+        acc, sums = np.zeros(Z.shape[1]), []
+        for j, (op, (x0, x1)) in enumerate(zip(batch, reads)):
+            for mask in (op[3], op[6], op[7]):
+                assert mask in (0, 0xFFFFFFFF)
+            acc = acc if (j > 0 and op[3]) else np.zeros(Z.shape[1])
+            if op[6]:
+                acc = acc + f32(op[4]) * x0
+            if op[7]:
+                acc = acc + f32(op[5]) * x1
+            sums.append(acc)
+        for op, a in zip(batch, sums):
+            assert int(op[2]) % 256 == 0
+            tile[int(op[2]) // 256] = a
+    return tile
+
+
+def test_consensus_program_on_the_host():
+    """What the one-launch form of the average consensus executes, interpreted on the CPU, against the factors
+    applied one after the other (and so against Lemma 1): rings, tori, a path, stars, random regular graphs up to
+    256 workers, several roots; and the cases it has to decline."""
+    rng = np.random.default_rng(11)
+    cases = [(D.Topology.ring(), 16, 0), (D.Topology.ring(), 31, 7), (D.Topology.torus(8, 8), 64, 0),
+             (D.Topology.torus(4, 8), 32, 13), (D.Topology.from_edges(gen.edges_path(9), D.DETAG_W_METROPOLIS), 9, 4),
+             (D.Topology.from_edges(np.array([[0, i] for i in range(1, 8)]), D.DETAG_W_METROPOLIS), 8, 0),
+             (D.Topology.from_edges(np.array([[0, i] for i in range(1, 8)]), D.DETAG_W_METROPOLIS), 8, 3),
+             (D.Topology.from_edges(gen.edges_random_regular(64, 4, 3), D.DETAG_W_METROPOLIS), 64, 9),
+             (D.Topology.from_edges(gen.edges_random_regular(256, 4, 5), D.DETAG_W_METROPOLIS), 256, 100),
+             (D.Topology.ring(), 2, 1), (D.Topology.ring(), 3, 0)]
+    for topo, n, root in cases:
+        ctx = D.detag_create(topo, n, 8)
+        f = D.Factors(ctx, root)
+        prog = f.program()
+        assert prog.shape[0] > 0 and prog.shape[0] % 2 == 0, (n, root)
+        Z = rng.standard_normal((n, 5))
+        ref = Z.copy()
+        changed = 0
+        for r in range(f.R):
+            A = f.dense(r)
+            changed += int(np.sum(np.any(A != np.eye(n), axis=1)))
+            ref = A @ ref
+        got = _run_program(prog, Z)
+        assert np.allclose(ref, Z.mean(0), rtol=0, atol=1e-14)
+        assert np.abs(got - ref).max() < 1e-6, (n, root)          # the program's weights are fp32
+        assert prog.shape[0] * 4 < 2 * changed + 8                # no more operations than changed rows call for
+        # an entry far from the others must not leak through an absent term: the masks, not the weights, drop it
+        Zbig = Z.copy(); Zbig[root, 0] = 1e30
+        assert np.all(np.isfinite(_run_program(prog, Zbig)))
+    # more than 8 terms in a factor row (a star's centre with 12 leaves) and more than 256 workers are declined
+    star = D.Topology.from_edges(np.array([[0, i] for i in range(1, 13)]), D.DETAG_W_METROPOLIS)
+    assert D.Factors(D.detag_create(star, 13, 8), 0).program().shape[0] == 0
+    assert D.Factors(D.detag_create(D.Topology.ring(), 300, 8), 0).program().shape[0] == 0
+    assert D.Factors(D.detag_create(D.Topology.ring(), 1, 8), 0).program().shape[0] == 0
+
+
 def test_asymmetric_W_is_accepted_without_eta():
     P = np.roll(np.eye(5), 1, axis=1)
     W = 0.5 * np.eye(5) + 0.5 * P
