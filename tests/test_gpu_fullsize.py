@@ -127,6 +127,39 @@ def test_config4_full_size_single_kernel_step():
     assert torch.equal(X, X2) and torch.equal(Y, Y2) and torch.equal(G, Gnew2)
 
 
+def test_config4_full_size_average_consensus():
+    """The exact average consensus (Lemma 1) on the benchmark's state matrix, in one launch and factor by factor:
+    sampled columns against the oracle's factor sequence, and, at any size, every row equal to the column mean."""
+    from oracle import consensus as OC
+    cfg = CONFIGS[4]
+    n, d, seed = cfg.n, cfg.d, cfg.seed
+    ld = D.padded_ld(d)
+    ctx = D.detag_create(D.Topology.torus(8, 8), n, d, ld)
+    f = D.Factors(ctx, 0)
+    factors = OC.gather_propagate_factors(n, gen.edges_torus(8, 8), 0)
+    assert f.R == len(factors) == 16 and f.program().shape[0] > 0
+    dev = torch.device(DEV)
+    Z = gen.device_normal(n, d, ld, seed, 7, dev)
+    cols = _sample_columns(d, np.random.default_rng(1))
+    idx = torch.from_numpy(cols).to(dev)
+    take = lambda t: t[:, idx].double().cpu().numpy()
+    Zs = take(Z)
+    ref = OC.average_consensus(Zs, factors)
+    mean_dev = ctx.mean(Z)[:d].double()
+    pad = Z[:, d:].clone()
+    Z1 = Z.clone()
+    f.average(Z1)                                               # one launch, rows in LDS
+    assert rel_err(take(Z1), ref, amax(Zs)) < TOL_F32
+    assert (Z1[:, :d].double() - mean_dev).abs().max().item() < 2e-6
+    assert torch.equal(Z1[:, d:], pad)
+    ctx.set_path(D.DETAG_PATH_PER_ROUND)                        # one launch per factor
+    Z2 = Z.clone()
+    f.average(Z2)
+    assert rel_err(take(Z2), ref, n * amax(Zs), floor=1.0) < TOL_F32
+    assert (Z2[:, :d].double() - mean_dev).abs().max().item() < 2e-6
+    assert torch.equal(Z2[:, d:], pad)
+
+
 def test_config5_full_size_sampled_columns():
     """n=256, the library's own random 4-regular graph (seeded) with Metropolis weights, d=1,048,576, bf16 X and
     Y, K=16: one phase from a mid-run state in the configuration bench.py --config 5 times.  The graph reaches
