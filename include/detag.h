@@ -103,7 +103,13 @@ typedef enum {
 typedef enum {
   DETAG_PATH_AUTO = 0,
   DETAG_PATH_PER_ROUND = 1, /* one launch per gossip round, state streamed through HBM every round */
-  DETAG_PATH_FUSED = 2      /* all K rounds on chip, one pass over the state; EUNSUPPORTED if n does not fit */
+  DETAG_PATH_FUSED = 2,     /* all K rounds on chip, one pass over the state; EUNSUPPORTED if n does not fit */
+  /* The K rounds as one product with the matrix polynomial of Algorithm 3, P = p_K(W^T),
+   * p_{k+1}(M) = (1+eta) M p_k(M) - eta p_{k-1}(M), p_0 = p_{-1} = I, on the matrix cores (n <= 256, else
+   * EUNSUPPORTED): same result up to rounding, cost independent of K and of the graph's degree.  Applies to
+   * detag_gossip_accel and detag_step; the first call with a new (K, eta) evaluates P on the host and uploads
+   * it (a blocking copy; the context keeps the last four).  AUTO never picks it. */
+  DETAG_PATH_DENSE = 3
 } detag_path;
 
 /*
@@ -152,6 +158,14 @@ detag_status detag_set_path(detag_ctx *ctx, detag_path path);
 
 /* 1 if the fused (all K rounds on chip) kernels exist for this context, else 0. */
 int32_t detag_has_fused(const detag_ctx *ctx);
+
+/*
+ * The matrix of K rounds of Algorithm 3 with momentum eta (eta < 0: the context's): AG_K(Z) = P Z with
+ * P = p_K(W^T), p_0 = p_{-1} = I, p_{k+1}(M) = (1+eta) M p_k(M) - eta p_{k-1}(M).  Host work only, fp64;
+ * P_out: n*n doubles, row-major, caller-owned.  For a symmetric W its singular values are |p_K(mu)| over W's
+ * eigenvalues mu, so it gives the exact contraction of the K rounds; DETAG_PATH_DENSE multiplies by it.
+ */
+detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double eta, double *P_out);
 
 /*
  * Accelerated gossip, Algorithm 3, for all workers at once, in place:

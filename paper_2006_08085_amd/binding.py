@@ -24,13 +24,13 @@ DETAG_F32, DETAG_BF16 = 0, 1
 DETAG_TOPO_RING, DETAG_TOPO_TORUS2D, DETAG_TOPO_RANDOM_REGULAR, DETAG_TOPO_EDGES, DETAG_TOPO_CSR = range(5)
 DETAG_W_UNIFORM, DETAG_W_METROPOLIS = 0, 1
 DETAG_VARIANT_ATC, DETAG_VARIANT_ALG2 = 0, 1
-DETAG_PATH_AUTO, DETAG_PATH_PER_ROUND, DETAG_PATH_FUSED = 0, 1, 2
+DETAG_PATH_AUTO, DETAG_PATH_PER_ROUND, DETAG_PATH_FUSED, DETAG_PATH_DENSE = 0, 1, 2, 3
 
 _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DETAG_EDISCONNECTED",
                  "DETAG_EUNSUPPORTED", "DETAG_ENOMEM", "DETAG_EHIP"]
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
-           "detag_get_phase_length", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
+           "detag_get_phase_length", "detag_get_gossip_polynomial", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
            "detag_factors_get_program",
            "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
     L.detag_get_spectrum.restype = C.c_int
     L.detag_get_phase_length.argtypes = [vp, f64, C.POINTER(i32)]
     L.detag_get_phase_length.restype = C.c_int
+    L.detag_get_gossip_polynomial.argtypes = [vp, i32, f64, C.POINTER(f64)]
+    L.detag_get_gossip_polynomial.restype = C.c_int
     L.detag_get_csr.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(C.POINTER(i32)),
                                 C.POINTER(C.POINTER(i32)), C.POINTER(C.POINTER(f64))]
     L.detag_get_csr.restype = C.c_int
@@ -307,6 +309,12 @@ class Context:
         self._check(lib().detag_get_phase_length(self._h, outer_ratio, C.byref(R)))
         return R.value
 
+    def gossip_polynomial(self, K: int, eta: float = -1.0) -> np.ndarray:
+        """P with AG_K(Z) = P Z (detag_get_gossip_polynomial), n x n fp64."""
+        P = np.empty((self.n, self.n), np.float64)
+        self._check(lib().detag_get_gossip_polynomial(self._h, K, eta, P.ctypes.data_as(C.POINTER(C.c_double))))
+        return P
+
     def csr(self):
         n, nnz = C.c_int32(), C.c_int64()
         rp, ci, va = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)(), C.POINTER(C.c_double)()
@@ -464,6 +472,7 @@ def detag_destroy(ctx: Context): ctx.close()
 def detag_get_spectrum(ctx: Context): return ctx.spectrum()
 def detag_get_csr(ctx: Context): return ctx.csr()
 def detag_get_phase_length(ctx: Context, outer_ratio=0.0): return ctx.phase_length(outer_ratio)
+def detag_get_gossip_polynomial(ctx: Context, K, eta=-1.0): return ctx.gossip_polynomial(K, eta)
 def detag_set_path(ctx: Context, path: int): ctx.set_path(path)
 def detag_has_fused(ctx: Context): return ctx.has_fused()
 def detag_gossip_accel(ctx: Context, Z, K, eta=-1.0): ctx.gossip_accel(Z, K, eta)

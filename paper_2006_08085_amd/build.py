@@ -19,7 +19,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdetag.so")
 
 SOURCES = ["topology.cpp", "consensus.cpp", "detag_api.hip", "k_stream.hip", "k_fused.hip", "k_fused_quad.hip", "k_fused_generic.hip",
-           "k_diag.hip", "k_grad.hip", "k_softmax.hip", "k_consensus.hip"]
+           "k_diag.hip", "k_grad.hip", "k_softmax.hip", "k_consensus.hip", "k_dense.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 VALU forms are kept off for every kernel in this library

@@ -31,6 +31,15 @@ struct detag_ctx {
   float *d_resid = nullptr;               // gradient scratch: least-squares residuals / softmax residuals
   int64_t resid_count = 0;
   detag_path path = DETAG_PATH_AUTO;
+  // DETAG_PATH_DENSE: the last few polynomials p_K(W^T) on the device
+  struct DensePoly {
+    int K = -1;
+    float eta = 0.f;
+    uint16_t *d_frag = nullptr;
+    uint64_t used = 0;
+  };
+  DensePoly poly[4];
+  uint64_t poly_clock = 0;
   mutable std::string err;
 };
 
@@ -114,11 +123,12 @@ DevCsr dev_csr(const detag_ctx *ctx) {
   return w;
 }
 
-enum Chosen { kPerRound, kFusedStructured, kFusedGeneric };
+enum Chosen { kPerRound, kFusedStructured, kFusedGeneric, kDense };
 
 detag_status choose_path(const detag_ctx *ctx, Chosen *out) {
   const bool fs = fused_structured_available(ctx->W), fg = ctx->fused_generic;
   if (ctx->path == DETAG_PATH_PER_ROUND) return *out = kPerRound, DETAG_OK;
+  if (ctx->path == DETAG_PATH_DENSE) return *out = kDense, DETAG_OK;
   if (fs) return *out = kFusedStructured, DETAG_OK;
   if (fg) return *out = kFusedGeneric, DETAG_OK;
   if (ctx->path == DETAG_PATH_FUSED)
@@ -127,6 +137,34 @@ detag_status choose_path(const detag_ctx *ctx, Chosen *out) {
 }
 
 Shape as_f32(Shape s) { return s.bf16 = false, s; }
+
+// The device copy of p_K(W^T) for DETAG_PATH_DENSE: from the context's small cache, or evaluated and uploaded now.
+// A buffer is rewritten only after the device has drained, since an earlier launch may still read it.
+detag_status dense_poly(detag_ctx *ctx, int K, float eta, const uint16_t **frag) {
+  detag_ctx::DensePoly *slot = nullptr;
+  for (auto &e : ctx->poly)
+    if (e.d_frag && e.K == K && e.eta == eta) slot = &e;
+  if (!slot) {
+    const int terms = dense_poly_terms(ctx->shape.bf16);
+    std::vector<uint16_t> host;
+    if (!build_dense_poly(ctx->W, K, double(eta), terms, host))
+      return set_err(ctx, DETAG_EUNSUPPORTED, "the dense path needs n <= 256");
+    for (auto &e : ctx->poly)
+      if (!slot || e.used < slot->used) slot = &e;  // least recently used (unused slots have used == 0)
+    hipError_t err = hipSuccess;
+    if (slot->d_frag) err = hipDeviceSynchronize();
+    else err = hipMalloc(reinterpret_cast<void **>(&slot->d_frag), host.size() * sizeof(uint16_t));
+    if (err == hipSuccess) err = hipMemcpy(slot->d_frag, host.data(), host.size() * sizeof(uint16_t), hipMemcpyHostToDevice);
+    if (err != hipSuccess) {
+      slot->K = -1;
+      return hip_fail(ctx, "uploading the gossip polynomial", int(err));
+    }
+    slot->K = K, slot->eta = eta;
+  }
+  slot->used = ++ctx->poly_clock;
+  *frag = slot->d_frag;
+  return DETAG_OK;
+}
 
 // Algorithm 3 with one launch per round on an fp32 matrix A.  z_r lives in A or
 // in scratch; a round may write over its own z_{r-1} (each output element reads
@@ -279,6 +317,7 @@ void detag_destroy(detag_ctx *ctx) {
     (void)hipFree(ctx->d_partials);
     (void)hipFree(ctx->d_resid);
     for (void *p : ctx->scratch) (void)hipFree(p);
+    for (auto &e : ctx->poly) (void)hipFree(e.d_frag);
   }
   delete ctx;
 }
@@ -319,8 +358,10 @@ detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const
 
 detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
   if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
-  if (path != DETAG_PATH_AUTO && path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_FUSED)
+  if (path != DETAG_PATH_AUTO && path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_FUSED && path != DETAG_PATH_DENSE)
     return set_err(ctx, DETAG_EINVAL, "unknown path");
+  if (path == DETAG_PATH_DENSE && ctx->W.n > 256)
+    return set_err(ctx, DETAG_EUNSUPPORTED, "the dense path needs n <= 256");
   if (path == DETAG_PATH_FUSED && !detag_has_fused(ctx))
     return set_err(ctx, DETAG_EUNSUPPORTED, "no fused kernel for this topology and n");
   ctx->path = path;
@@ -330,6 +371,22 @@ detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
 int32_t detag_has_fused(const detag_ctx *ctx) {
   if (!ctx) return 0;
   return fused_structured_available(ctx->W) || ctx->fused_generic ? 1 : 0;
+}
+
+detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double eta, double *P_out) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (!P_out) return set_err(ctx, DETAG_EINVAL, "P_out is NULL");
+  if (K < 0) return set_err(ctx, DETAG_EINVAL, "K must be >= 0");
+  float e;
+  if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
+  std::vector<double> P;
+  try {
+    gossip_polynomial(ctx->W, K, eta < 0 ? ctx->W.eta : eta, P);
+  } catch (const std::bad_alloc &) {
+    return set_err(ctx, DETAG_ENOMEM, "out of host memory");
+  }
+  std::copy(P.begin(), P.end(), P_out);
+  return DETAG_OK;
 }
 
 detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double eta, void *stream) {
@@ -349,6 +406,12 @@ detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double e
     case kFusedGeneric:
       rc = launch_fused_generic(ctx->shape, ctx->W, dev_csr(ctx), 0, Z_dev, nullptr, nullptr, nullptr, 0.f, K, e, stream);
       break;
+    case kDense: {
+      const uint16_t *frag = nullptr;
+      if (detag_status st = dense_poly(ctx, K, e, &frag)) return st;
+      rc = launch_dense_phase(ctx->shape, 0, Z_dev, nullptr, nullptr, nullptr, 0.f, frag, stream);
+      break;
+    }
     case kPerRound: {
       WideState ws{ctx};
       if (detag_status st = ws.open(Z_dev, nullptr, stream)) return st;
@@ -400,6 +463,12 @@ detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *G
   if (path == kFusedGeneric) {
     const int rc = launch_fused_generic(s, ctx->W, dev_csr(ctx), mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, K, e, stream);
     return rc ? hip_fail(ctx, "fused phase", rc) : DETAG_OK;
+  }
+  if (path == kDense) {
+    const uint16_t *frag = nullptr;
+    if (detag_status st = dense_poly(ctx, K, e, &frag)) return st;
+    const int rc = launch_dense_phase(s, mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, frag, stream);
+    return rc ? hip_fail(ctx, "dense phase", rc) : DETAG_OK;
   }
   WideState ws{ctx};
   if (detag_status st = ws.open(X_dev, Y_dev, stream)) return st;

@@ -84,6 +84,16 @@ struct Shape {
 // Z <- A_{R-1} ... A_0 Z on chip, in place (table from build_factor_table).  -1 if n rows of 64 columns do not
 // fit a block's LDS on this device.
 int launch_factor_sequence(const Shape &s, const uint32_t *table, int table_words, void *Z, void *stream);
+// The matrix polynomial of K rounds of Algorithm 3, P = p_K(W^T), as bf16 terms in the operand order of
+// dense_phase_kernel (`terms` = dense_poly_terms(state type), dense_poly_words(terms) 16-bit words).  false if n > 256.
+void gossip_polynomial(const HostW &W, int K, double eta, std::vector<double> &P);  // n x n, row-major, fp64
+int dense_poly_terms(bool bf16_state);
+size_t dense_poly_words(int terms);
+bool build_dense_poly(const HostW &W, int K, double eta, int terms, std::vector<uint16_t> &frag);
+// One phase with P: mode 0: X <- P X.  mode 1: X <- P (X - alpha*Y), Y <- P (Y + Gn - Go).
+// mode 2: X <- P X - alpha * P Y, Y <- P Y + Gn - Go.  n <= 256.
+int launch_dense_phase(const Shape &s, int mode, void *X, void *Y, const float *Gn, const float *Go, float alpha,
+                       const uint16_t *frag, void *stream);
 // out = A cur for a CSR matrix A whose rows need not sum to one (row i lists (j, A_ij)); out != cur.
 int launch_spmm(const Shape &s, const DevCsr &a, const void *cur, void *out, void *stream);
 // X = Xt - scale*G; Xt = X; G = 0   (X may be Xt)

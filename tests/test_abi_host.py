@@ -209,6 +209,39 @@ def test_consensus_program_on_the_host():
     assert D.Factors(D.detag_create(D.Topology.ring(), 1, 8), 0).program().shape[0] == 0
 
 
+def test_gossip_polynomial_on_the_host():
+    """detag_get_gossip_polynomial against the oracle's Algorithm 3 run on the identity, and against what the
+    paper says about it: P 1 = 1 and 1^T P = 1^T (the worker mean is kept), K = 0 gives I, eta = 0 gives (W^T)^K,
+    and on a symmetric W its singular values are |p_K(mu)| over W's eigenvalues mu."""
+    from oracle import gossip as OG
+    cases = [(D.Topology.ring(), 8, T.mixing_matrix(8, gen.edges_ring(8))),
+             (D.Topology.torus(8, 8), 64, T.mixing_matrix(64, gen.edges_torus(8, 8))),
+             (D.Topology.from_edges(gen.edges_random_regular(40, 4, 2), D.DETAG_W_METROPOLIS), 40,
+              T.mixing_matrix(40, gen.edges_random_regular(40, 4, 2), "metropolis"))]
+    for topo, n, W in cases:
+        ctx = D.detag_create(topo, n, 8)
+        eta = T.eta_from_lambda(T.spectrum(W)[2])
+        for K in (0, 1, 2, 7, 16):
+            P = ctx.gossip_polynomial(K)
+            ref = OG.accelerated_gossip(np.eye(n), W, K, eta)
+            assert np.abs(P - ref).max() < 1e-13
+            assert np.abs(P.sum(0) - 1).max() < 1e-13 and np.abs(P.sum(1) - 1).max() < 1e-13
+            mu = np.linalg.eigvalsh(W)
+            pk_prev, pk = np.ones_like(mu), np.ones_like(mu)
+            for _ in range(K):
+                pk_prev, pk = pk, (1 + eta) * mu * pk - eta * pk_prev
+            assert np.allclose(np.linalg.svd(P, compute_uv=False), np.sort(np.abs(pk))[::-1], rtol=0, atol=1e-12)
+        assert np.array_equal(ctx.gossip_polynomial(0), np.eye(n))
+        assert np.abs(ctx.gossip_polynomial(3, 0.0) - np.linalg.matrix_power(W.T, 3)).max() < 1e-14
+    asym = 0.5 * np.eye(5) + 0.5 * np.roll(np.eye(5), 1, axis=1)
+    ctx = D.detag_create(D.Topology.from_dense(asym), 5, 8)
+    assert np.abs(ctx.gossip_polynomial(4, 0.2) - OG.accelerated_gossip(np.eye(5), asym, 4, 0.2)).max() < 1e-14
+    with pytest.raises(D.DetagError):
+        ctx.gossip_polynomial(4)          # no stored eta for an asymmetric W
+    with pytest.raises(D.DetagError):
+        ctx.gossip_polynomial(-1, 0.2)
+
+
 def test_asymmetric_W_is_accepted_without_eta():
     P = np.roll(np.eye(5), 1, axis=1)
     W = 0.5 * np.eye(5) + 0.5 * P
