@@ -82,6 +82,9 @@ def main():
                     help="detag (default, the headline line); dsgt = the same kernels with K=1, eta=0; dpsgd = "
                          "detag_grad_quadratic_diag + detag_dpsgd_step.  The two baselines of the paper's "
                          "Experiments section, timed on the same workload")
+    ap.add_argument("--dense", action="store_true",
+                    help="run detag_step on DETAG_PATH_DENSE (the K rounds as one matrix-core product with the "
+                         "polynomial p_K(W^T)); for the unfused step only, i.e. --config 5 or --unfused")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of one n x ld fp32 matrix (a kernel of known "
                          "traffic, for scaling profiler byte counters); untimed")
@@ -131,6 +134,11 @@ def main():
 
     state = {"t": 0, "Ga": Ga, "Gb": Gb}
     fused = not args.unfused and alg != "dpsgd" and structured
+    if args.dense:
+        if fused or alg == "dpsgd":
+            print("bench.py: --dense applies to the two-kernel step (--config 5, or --unfused)", file=sys.stderr)
+            sys.exit(2)
+        ctx.set_path(D.DETAG_PATH_DENSE)
 
     def one_step(ev=None):
         if alg == "dpsgd":
@@ -198,18 +206,22 @@ def main():
                    "algorithm": alg,
                    "step": "detag_grad_quadratic_diag + detag_dpsgd_step" if alg == "dpsgd"
                            else "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
+                           else "detag_grad_quadratic_diag + detag_step (ATC, one product with p_K(W^T))" if args.dense
                            else "detag_grad_quadratic_diag + detag_step (ATC, fused K rounds)",
                    "finite": finite},
         "roofline": {"bound": "hbm",
                      "kernel": ("fused_structured_kernel, D-PSGD mode" if structured else "gossip_round_kernel")
                                + " (detag_dpsgd_step)" if alg == "dpsgd"
                                else "fused_quadratic_kernel (detag_step_quadratic)" if fused
+                               else "dense_phase_kernel (detag_step)" if args.dense
                                else ("fused_structured_kernel" if structured else "fused_generic_kernel") + " (detag_step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(fused) if args.config == 4 and alg == "detag" else None, "kernel_ms": phase_ms,
                      "algorithmic_bytes_per_launch": bpe * n * d,
-                     **({} if structured else {"note": "this kernel keeps all rows of a tile in LDS and is bound by "
-                                                        "LDS bandwidth and VALU issue, not by HBM"})},
+                     **({"note": "bound by the latency of its staging loads and by instruction issue, not yet by HBM "
+                                 "or the matrix cores"} if args.dense else {} if structured
+                        else {"note": "this kernel keeps all rows of a tile in LDS and is bound by "
+                                      "LDS bandwidth and VALU issue, not by HBM"})},
     }
     if not args.no_cpu_baseline and alg == "detag":
         out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample_cols, d), ctx.dense_W())

@@ -91,7 +91,7 @@ int dense_poly_terms(bool bf16_state);
 size_t dense_poly_words(int terms);
 bool build_dense_poly(const HostW &W, int K, double eta, int terms, std::vector<uint16_t> &frag);
 // One phase with P: mode 0: X <- P X.  mode 1: X <- P (X - alpha*Y), Y <- P (Y + Gn - Go).
-// mode 2: X <- P X - alpha * P Y, Y <- P Y + Gn - Go.  n <= 256.
+// mode 2: X <- P X - alpha * P Y (evaluated as P (X - alpha*Y)), Y <- P Y + Gn - Go.  n <= 256.
 int launch_dense_phase(const Shape &s, int mode, void *X, void *Y, const float *Gn, const float *Go, float alpha,
                        const uint16_t *frag, void *stream);
 // out = A cur for a CSR matrix A whose rows need not sum to one (row i lists (j, A_ij)); out != cur.
