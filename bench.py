@@ -208,6 +208,7 @@ def main():
                            else "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
                            else "detag_grad_quadratic_diag + detag_step (ATC, one product with p_K(W^T))" if args.dense
                            else "detag_grad_quadratic_diag + detag_step (ATC, fused K rounds)",
+                   "matrix_rounds_per_s": 2 * n * d * K / (dt / args.steps),   # X and Y counted separately
                    "finite": finite},
         "roofline": {"bound": "hbm",
                      "kernel": ("fused_structured_kernel, D-PSGD mode" if structured else "gossip_round_kernel")

@@ -160,10 +160,12 @@ def test_config4_full_size_average_consensus():
     assert torch.equal(Z2[:, d:], pad)
 
 
-def test_config5_full_size_sampled_columns():
+@pytest.mark.parametrize("path", ["rounds", "dense"])
+def test_config5_full_size_sampled_columns(path):
     """n=256, the library's own random 4-regular graph (seeded) with Metropolis weights, d=1,048,576, bf16 X and
-    Y, K=16: one phase from a mid-run state in the configuration bench.py --config 5 times.  The graph reaches
-    the oracle as data (the library's CSR), re-validated there."""
+    Y, K=16: one phase from a mid-run state in the configurations bench.py --config 5 times (the K rounds on
+    chip, and with --dense as one product with the gossip polynomial).  The graph reaches the oracle as data (the
+    library's CSR), re-validated there."""
     cfg = CONFIGS[5]
     n, d, K, alpha, seed = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.seed
     ld = D.padded_ld(d)
@@ -185,6 +187,8 @@ def test_config5_full_size_sampled_columns():
     idx = torch.from_numpy(cols).to(dev)
     take = lambda t: t[:, idx].double().cpu().numpy()
     Xs, Ys, Gns, Gos = take(X), take(Y), take(Gn), take(Go)
+    if path == "dense":
+        ctx.set_path(D.DETAG_PATH_DENSE)
     ctx.step(X, Y, Gn, Go, alpha, K)
     Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
     S = amax(Xs, Ys, Gns, Gos)
