@@ -225,7 +225,7 @@ __device__ __forceinline__ void pass(f32x16 (&acc)[2][2], uint16_t *stage, bool 
                                      const ST *X, const ST *Y, const float *Gn, const float *Go, int n, int64_t tile,
                                      int64_t ld, uint32_t valid, float alpha, const u16x8 *__restrict__ frag) {
   using G = Geo<KS>;
-  constexpr int kDepth = TP >= 3 ? 2 : (G::KU < 3 ? G::KU : 3);
+  constexpr int kDepth = 2;  // k-steps the rows of P are requested ahead (three cost registers, and spills, for nothing)
 #pragma unroll
   for (int u = 0; u < G::kUnits; ++u) {
     if (u > 0 || !fresh) __syncthreads();  // every wavefront is done with what LDS held
