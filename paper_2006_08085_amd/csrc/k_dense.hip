@@ -17,7 +17,8 @@
 // term).  An infinite input leaves NaN in its column (Inf - Inf in the split),
 // where the round-by-round kernels leave Inf or NaN.
 //
-// One block = 64 columns, 4 wavefronts, three blocks to a compute unit.  The input of a pass is staged in units of
+// One block = 64 columns, 4 wavefronts, three blocks to a compute unit (two with fp32 state, whose three-term
+// operands need the registers).  The input of a pass is staged in units of
 // 128 workers.  Staging: lane = column, a wavefront loads groups of 8 consecutive rows (coalesced row segments),
 // applies the phase's elementwise part (X - alpha Y, Y + Gnew - Gold), splits, and writes one 16-byte word per
 // term to LDS laid out [term][column][row] -- exactly the B operand (column m, k = 8g..8g+7) of the MFMA.
@@ -271,7 +272,7 @@ __device__ __forceinline__ void write_out(const f32x16 (&acc)[2][2], float *scra
 // mode 2 (ALG2): X <- P X - alpha * P Y = P (X - alpha*Y) (P is linear), Y <- P Y + Gn - Go.  n <= 16 KS.
 // A pass writes its result once every wavefront has staged all the pass reads of the array it overwrites.
 template <typename ST, int TP, int TU, int MODE, int KS>
-__global__ __launch_bounds__(kThreads, 3) void dense_phase_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
+__global__ __launch_bounds__(kThreads, TP >= 3 ? 2 : 3) void dense_phase_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
                                                                   const float *__restrict__ Go, int n, int64_t d,
                                                                   int64_t ld, const u16x8 *__restrict__ frag,
                                                                   float alpha) {
