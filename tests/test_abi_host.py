@@ -209,6 +209,47 @@ def test_consensus_program_on_the_host():
     assert D.Factors(D.detag_create(D.Topology.ring(), 1, 8), 0).program().shape[0] == 0
 
 
+def test_consensus_program_on_random_graphs():
+    """The same check on seeded random connected graphs of bounded degree (a random spanning tree plus extra edges),
+    random roots: whenever the library offers a program it reproduces the factor sequence, and it offers one exactly
+    when no factor row has more than 8 terms."""
+    rng = np.random.default_rng(2024)
+    offered = declined = 0
+    for trial in range(40):
+        n = int(rng.integers(2, 70))
+        max_deg = int(rng.integers(3, 12))
+        deg = np.zeros(n, int)
+        edges = set()
+        hub = trial % 5 == 0 and n >= 12                        # every fifth graph has a node with 10 neighbours
+        for v in range(1, n):                                   # random tree: attach v to an earlier node with room
+            cand = [u for u in range(v) if deg[u] < max_deg]
+            u = 0 if hub and v <= 10 else int(rng.choice(cand))
+            edges.add((u, v)); deg[u] += 1; deg[v] += 1
+        for _ in range(n):                                      # a few extra edges
+            a, b = sorted(int(x) for x in rng.integers(0, n, 2))
+            if a != b and (a, b) not in edges and deg[a] < max_deg and deg[b] < max_deg:
+                edges.add((a, b)); deg[a] += 1; deg[b] += 1
+        topo = D.Topology.from_edges(np.array(sorted(edges)), D.DETAG_W_METROPOLIS)
+        ctx = D.detag_create(topo, n, 8)
+        root = 0 if hub else int(rng.integers(0, n))
+        f = D.Factors(ctx, root)
+        widest = max(int(np.count_nonzero(f.dense(r), axis=1).max()) for r in range(f.R))
+        prog = f.program()
+        if widest > 8:
+            assert prog.shape[0] == 0
+            declined += 1
+            continue
+        offered += 1
+        assert prog.shape[0] > 0
+        Z = rng.standard_normal((n, 3))
+        ref = Z.copy()
+        for r in range(f.R):
+            ref = f.dense(r) @ ref
+        assert np.allclose(ref, Z.mean(0), rtol=0, atol=1e-13)
+        assert np.abs(_run_program(prog, Z) - ref).max() < 1e-6, (trial, n, root)
+    assert offered >= 10 and declined >= 3                      # the sweep reaches both outcomes
+
+
 def test_gossip_polynomial_on_the_host():
     """detag_get_gossip_polynomial against the oracle's Algorithm 3 run on the identity, and against what the
     paper says about it: P 1 = 1 and 1^T P = 1^T (the worker mean is kept), K = 0 gives I, eta = 0 gives (W^T)^K,
