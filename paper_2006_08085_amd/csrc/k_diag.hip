@@ -18,7 +18,8 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(int n, int64_t d, int64_
   const int64_t c = int64_t(blockIdx.x) * kThreads + threadIdx.x;
   if (c >= d) return;
   double s = 0.0;
-  for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));
+#pragma unroll 16
+  for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));  // 16 rows' loads in flight
   xbar[c] = float(s / n);
 }
 
@@ -42,8 +43,10 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(int n, int6
   double acc = 0.0;
   if (c < d) {
     double s = 0.0;
+#pragma unroll 16
     for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));
     const double m = s / n;
+#pragma unroll 16
     for (int i = 0; i < n; ++i) {
       const double dev = double(to_f32(X[int64_t(i) * ld + c])) - m;
       acc += dev * dev;
