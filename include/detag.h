@@ -298,6 +298,25 @@ detag_status detag_mean(detag_ctx *ctx, const void *X_dev, float *xbar_dev, void
 detag_status detag_consensus_error(detag_ctx *ctx, const void *X_dev, double *sumsq_dev, void *stream);
 
 /*
+ * detag_consensus_error for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same kernels, same reduction order and same result, with the
+ * per-block partial sums kept in an array that is part of the library's code
+ * object (512 KiB on every GPU the library runs on, held until the process
+ * ends) instead of memory owned by the context.  The call allocates and frees
+ * nothing and does not synchronise.
+ *   - d <= 16,777,216 (65,536 partial sums, one per 256 columns); a wider
+ *     context gets DETAG_EUNSUPPORTED and nothing is enqueued.
+ *   - All calls on one GPU, from every context, share that GPU's array.  Every
+ *     slot a call reads it has written itself, so nothing needs clearing
+ *     between calls; but two calls whose work overlaps in time on one GPU
+ *     (two streams, two threads, two contexts) race and give garbage: order
+ *     them on one stream or with events.
+ *   - The device that is current at the call must be the one X_dev lives on.
+ */
+detag_status detag_consensus_error_static(detag_ctx *ctx, const void *X_dev, double *sumsq_dev, void *stream);
+
+/*
  * Stochastic gradient of f_i(x) = 1/2 sum_c h_c (x_c - b_ic)^2 at every
  * worker's own model (the gradient query of Algorithm 2):
  *   G[i,c] = h[c]*(X[i,c] - b[i,c]) + sigma * z[i,c]

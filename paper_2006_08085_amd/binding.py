@@ -34,7 +34,7 @@ EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
            "detag_factors_get_program",
            "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
-           "detag_mean", "detag_consensus_error", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
+           "detag_mean", "detag_consensus_error", "detag_consensus_error_static", "detag_grad_quadratic_diag", "detag_step_quadratic", "detag_grad_lstsq",
            "detag_grad_softmax_bf16", "detag_last_error", "detag_version"]
 
 
@@ -116,6 +116,8 @@ def lib() -> C.CDLL:
     L.detag_mean.restype = C.c_int
     L.detag_consensus_error.argtypes = [vp, vp, vp, vp]
     L.detag_consensus_error.restype = C.c_int
+    L.detag_consensus_error_static.argtypes = [vp, vp, vp, vp]
+    L.detag_consensus_error_static.restype = C.c_int
     L.detag_grad_quadratic_diag.argtypes = [vp, vp, vp, i32, vp, vp, f32, u64, u32, vp, vp]
     L.detag_grad_quadratic_diag.restype = C.c_int
     L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, vp, f32, u64, u32, f64, i32, f64, vp]
@@ -398,6 +400,16 @@ class Context:
                                                 self._stream()))
         return out
 
+    def consensus_error_static(self, X, out):
+        """detag_consensus_error_static: `out` (one float64 on the GPU) is required, since this call is for
+        callers that may not allocate."""
+        import torch
+        if out.dtype != torch.float64 or not out.is_cuda or out.numel() < 1:
+            raise ValueError("out must be a float64 GPU tensor with at least one element")
+        self._check(lib().detag_consensus_error_static(self._h, self._state(X, "X"), C.c_void_p(out.data_ptr()),
+                                                       self._stream()))
+        return out
+
     # -- gradients ---------------------------------------------------------------
     def grad_quadratic_diag(self, X, h, b, G, noise=None, sigma: float = 0.0, seed: int = 0, step: int = 0):
         import torch
@@ -493,6 +505,7 @@ def detag_average_consensus(ctx: Context, f: Factors, Z): f.average(Z)
 def detag_defacto_update(ctx: Context, X, X_tilde, G, scale): ctx.defacto_update(X, X_tilde, G, scale)
 def detag_mean(ctx: Context, X, out=None): return ctx.mean(X, out)
 def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error(X, out)
+def detag_consensus_error_static(ctx: Context, X, out): return ctx.consensus_error_static(X, out)
 def detag_grad_quadratic_diag(ctx: Context, X, h, b, G, noise=None, sigma=0.0, seed=0, step=0):
     ctx.grad_quadratic_diag(X, h, b, G, noise, sigma, seed, step)
 def detag_step_quadratic(ctx: Context, X, Y, G, h, b, alpha, K, sigma=0.0, seed=0, step=0, eta=-1.0):

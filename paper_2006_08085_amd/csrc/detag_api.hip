@@ -279,6 +279,9 @@ detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int6
   }
   ctx->has_device = true;
   (void)hipGetDevice(&ctx->device);
+  // address of the library-resident partial sums on this device (detag_consensus_error_static); a failure is
+  // reported by that entry point, which looks the address up again
+  if (static_partials_init(ctx->device) != 0) (void)hipGetLastError();
   const size_t nnz = ctx->W.colidx.size();
   std::vector<float> vals32(nnz);
   for (size_t k = 0; k < nnz; ++k) vals32[k] = float(ctx->W.vals[k]);
@@ -705,6 +708,22 @@ detag_status detag_consensus_error(detag_ctx *ctx, const void *X_dev, double *su
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
   if (!sumsq_dev || misaligned(sumsq_dev, 8)) return set_err(ctx, DETAG_EINVAL, "sumsq_dev is NULL or misaligned");
   const int rc = launch_consensus_error(ctx->shape, X_dev, ctx->d_partials, sumsq_dev, stream);
+  return rc ? hip_fail(ctx, "consensus error", rc) : DETAG_OK;
+}
+
+detag_status detag_consensus_error_static(detag_ctx *ctx, const void *X_dev, double *sumsq_dev, void *stream) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
+  if (!sumsq_dev || misaligned(sumsq_dev, 8)) return set_err(ctx, DETAG_EINVAL, "sumsq_dev is NULL or misaligned");
+  if (consensus_partials_count(ctx->shape) > kStaticPartialsMax)
+    return set_err(ctx, DETAG_EUNSUPPORTED,
+                   "detag_consensus_error_static holds partial sums for d <= 16,777,216 columns; "
+                   "use detag_consensus_error for wider matrices");
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return hip_fail(ctx, "hipGetDevice", int(e));
+  if (!static_partials(dev))
+    if (int rc = static_partials_init(dev)) return hip_fail(ctx, "looking up the resident partial sums", rc);
+  const int rc = launch_consensus_error(ctx->shape, X_dev, static_partials(dev), sumsq_dev, stream);
   return rc ? hip_fail(ctx, "consensus error", rc) : DETAG_OK;
 }
 

@@ -135,6 +135,12 @@ int launch_fused_generic(const Shape &s, const HostW &W, const DevCsr &w, int mo
 int launch_mean(const Shape &s, const void *X, float *xbar, void *stream);
 int64_t consensus_partials_count(const Shape &s);
 int launch_consensus_error(const Shape &s, const void *X, double *partials, double *out, void *stream);
+// The library-resident partial-sum array of detag_consensus_error_static: kStaticPartialsMax doubles per GPU.
+// static_partials_init looks its address up on `device` (which must be current), once; static_partials returns
+// that address, or nullptr before a successful init.
+constexpr int64_t kStaticPartialsMax = 65536;  // 512 KiB; one slot per 256 columns: d <= 16,777,216
+int static_partials_init(int device);
+double *static_partials(int device);
 
 // Gradients
 int launch_grad_quadratic(const Shape &s, const void *X, const float *h, int h_per_worker, const float *b,

@@ -64,7 +64,30 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(int64_t count, c
   if (threadIdx.x == 0) *out = t;
 }
 
+// Partial sums of detag_consensus_error_static: one slot per block of 256 columns.  The array is part of the
+// library's code object, so every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels receive the address
+// that call returns.
+__device__ __align__(256) double scratch[kStaticPartialsMax];
+
+constexpr int kMaxDevices = 64;
+double *g_scratch_ptr[kMaxDevices] = {};  // per device, set once by static_partials_init
+
 }  // namespace
+
+int static_partials_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return hip_rc(hipErrorInvalidDevice);
+  if (g_scratch_ptr[device]) return 0;
+  double *ptr = nullptr;
+  const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return hip_rc(e);
+  g_scratch_ptr[device] = ptr;
+  return 0;
+}
+
+double *static_partials(int device) {
+  return device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr;
+}
 
 int launch_mean(const Shape &s, const void *X, float *xbar, void *stream) {
   const dim3 grid(ceil_div_i64(s.d, kThreads));
