@@ -15,3 +15,27 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_terminal_summary(terminalreporter, exitstatus, config):
+    """Margins of the parity gate: for every test that compared against the oracle, the worst error under the
+    asserted floor and under tighter ones (see tests/util.py).  Also written to gpurun_out/parity_margins.txt
+    when that folder exists."""
+    try:
+        from tests.util import MARGINS
+    except Exception:
+        return
+    if not MARGINS:
+        return
+    cols = ["gate", "floor_S/16", "floor_S/64", "floor_1e-3_ref", "normwise_S", "normwise_ref"]
+    lines = ["test | comparisons | asserted floor | " + " | ".join(cols)]
+    for key in sorted(MARGINS):
+        test, m = key[0], MARGINS[key]
+        lines.append(f"{test} | {m['count']} | {m['floor']:.4g} | " + " | ".join(f"{m[c]:.3e}" for c in cols))
+    terminalreporter.write_sep("-", "parity margins (worst per test)")
+    for l in lines:
+        terminalreporter.write_line(l)
+    out = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "parity_margins.txt"), "w") as f:
+            f.write("\n".join(lines) + "\n")

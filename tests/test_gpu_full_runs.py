@@ -1,0 +1,237 @@
+"""Every workload run to its own number of steps T against the fp64 oracle.
+
+Algorithm 2 returns the worker mean after T iterations, so parity is checked
+where the method ends, not only after a step: entry by entry after the first
+step from identical inputs, normwise at T, and after EVERY step the two
+identities the proof of Theorem 3 rests on, evaluated on the device state:
+
+  tracker identity   mean_i Y_{k+1} = mean_i g_i(X_k)              (the last gradient the tracker absorbed)
+  mean iterate       mean_i X_{k+1} = mean_i X_k - alpha * mean_i Y_k
+
+For the diagonal quadratic with shared curvature h both combine into a scalar
+recurrence per column that does not involve the topology at all,
+  xbar_{k+1} = xbar_k - alpha * (h * (xbar_{k-1} - bbar) + sigma * zbar_{k-1}),   xbar_1 = xbar_0,
+which is evaluated here in fp64 and compared with the device's worker mean at T.
+
+Columns are independent for the quadratic objectives, so the oracle follows a
+sample of columns (first tiles, tile boundaries, the ragged tail, random ones)
+exactly while the GPU runs the whole matrix at its stated size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_08085_amd as D
+from oracle import gossip as OG
+from oracle import noise as ON
+from oracle import objectives as OO
+from oracle import topology as OT
+from tests.gpu_util import DEV, _built  # noqa: F401
+from tests.util import TOL_BF16, TOL_F32, amax, rel_err
+from workloads import CONFIGS, generate as gen
+
+pytestmark = pytest.mark.gpu
+
+
+def _columns(d, tile, count, seed):
+    head = list(range(0, min(d, 2 * tile + 2)))
+    tail = list(range(max(0, (d // tile) * tile - 3), d))
+    mid = [k * tile + o for k in (7, d // (2 * tile)) for o in (-1, 0, 1) if 0 <= k * tile + o < d]
+    rnd = np.random.default_rng(seed).integers(0, d, size=count).tolist()
+    return np.unique(np.array(head + tail + mid + rnd, dtype=np.int64))
+
+
+def _recurrence(xbar0, bbar, h, alpha, sigma, zbar, T):
+    """Worker mean of the diagonal quadratic after T steps from Y_0 = 0, g(-1) = 0 (fp64, topology-free)."""
+    prev, cur = xbar0.copy(), xbar0.copy()                       # xbar_0, xbar_1 = xbar_0
+    for k in range(1, T):
+        prev, cur = cur, cur - alpha * (h * (prev - bbar) + sigma * zbar[k - 1])
+    return cur
+
+
+class _QuadraticRun:
+    """Device matrices of a diagonal-quadratic workload at full size, drawn on the device, with the sampled
+    columns mirrored on the host for the oracle."""
+
+    def __init__(self, cfg, topo, tile, state_dtype=torch.float32, samples=1500):
+        self.cfg = cfg
+        n, d = cfg.n, cfg.d
+        self.n, self.d, self.ld = n, d, D.padded_ld(d)
+        self.bf16 = state_dtype == torch.bfloat16
+        self.ctx = D.detag_create(topo, n, d, self.ld, D.DETAG_BF16 if self.bf16 else D.DETAG_F32)
+        self.W = self.ctx.dense_W()                              # the graph reaches the oracle as data
+        OT.check_gossip_matrix(self.W)
+        self.eta = OT.eta_from_lambda(OT.spectrum(self.W)[2])
+        assert self.ctx.spectrum()["eta"] == pytest.approx(self.eta, abs=1e-12)
+        dev = torch.device(DEV)
+        ex = cfg.extra
+        self.b = gen.device_normal(n, d, self.ld, cfg.seed, 1, dev, std=ex["b_std"])
+        if ex.get("b_mean") == "i/n":
+            self.b[:, :d] += (torch.arange(n, device=dev, dtype=torch.float32) / n)[:, None]
+        self.h = gen.device_log_uniform(d, self.ld, cfg.seed, 2, dev, ex["h_lo"], ex["h_hi"])
+        self.X = D.new_matrix(n, d, self.ld, dtype=state_dtype, device=dev)     # x_0 = 0
+        self.Y = D.new_matrix(n, d, self.ld, dtype=state_dtype, device=dev)     # y_0 = 0
+        self.cols = _columns(d, tile, samples, seed=cfg.seed)
+        self.idx = torch.from_numpy(self.cols).to(dev)
+        self.bs, self.hs = self.take(self.b), self.h[self.idx].double().cpu().numpy()
+
+    def take(self, t):
+        return t[:, self.idx].double().cpu().numpy()
+
+    def oracle(self, T, sigma):
+        """The oracle's trajectory on the sampled columns: per step (X, Y, G_new) after the step; stored
+        state rounded to bf16 after each step when the device stores bf16."""
+        n, cols, cfg = self.n, self.cols, self.cfg
+        X = np.zeros((n, len(cols))); Y = np.zeros_like(X); Gold = np.zeros_like(X)
+        traj, zbar = [], []
+        for t in range(T):
+            z = ON.normal_noise(cfg.seed, t, n, cols) if sigma else None
+            zbar.append(z.mean(0) if sigma else np.zeros(len(cols)))
+            Gn = OO.grad_quadratic_diag(X, self.hs, self.bs, z, sigma)
+            Xn, Yn = OG.detag_step(X, Y, Gn, Gold, self.W, cfg.lr, cfg.K, self.eta)
+            raw = (Xn, Yn)
+            if self.bf16:
+                Xn, Yn = (OO.round_bf16(a).astype(np.float64) for a in (Xn, Yn))
+            traj.append(dict(X=Xn, Y=Yn, G=Gn, raw=raw, S_in=amax(X, Y, Gn, Gold)))
+            X, Y, Gold = Xn, Yn, Gn
+        return traj, zbar
+
+
+def _check_run(run, traj, zbar, T, sigma, do_step, gradient_of, tol, inv_tol):
+    """Drive T device steps; after each: the two identities on the device state (sampled columns); after the
+    first: entry by entry; at T: normwise, the worker mean against the scalar recurrence."""
+    cfg, alpha = run.cfg, run.cfg.lr
+    xbar_prev, ybar_prev = run.take(run.X).mean(0), run.take(run.Y).mean(0)
+    worst_track = worst_mean = 0.0
+    for t in range(T):
+        do_step(t)
+        Xg, Yg, Gg = run.take(run.X), run.take(run.Y), run.take(gradient_of())
+        S = max(traj[t]["S_in"], 1e-30)
+        worst_track = max(worst_track, np.abs(Yg.mean(0) - Gg.mean(0)).max() / S)
+        worst_mean = max(worst_mean, np.abs(Xg.mean(0) - (xbar_prev - alpha * ybar_prev)).max() / S)
+        xbar_prev, ybar_prev = Xg.mean(0), Yg.mean(0)
+        if t == 0:                                               # one step from identical inputs: entry by entry
+            assert rel_err(Gg, traj[0]["G"], S) < TOL_F32
+            assert rel_err(Xg, traj[0]["raw"][0], S) < tol
+            assert rel_err(Yg, traj[0]["raw"][1], S) < tol
+    assert worst_track < inv_tol, f"tracker identity off by {worst_track:.3e} of the state's scale"
+    assert worst_mean < inv_tol, f"mean-iterate identity off by {worst_mean:.3e} of the state's scale"
+    last = traj[T - 1]
+    S = amax(last["X"], last["Y"], last["G"])
+    assert rel_err(Xg, last["X"], S, floor=1.0) < tol
+    assert rel_err(Yg, last["Y"], S, floor=1.0) < tol
+    # the output of Algorithm 2 (full width on the device) against the topology-free recurrence
+    xhat = run.ctx.mean(run.X)[run.idx].double().cpu().numpy()
+    want = _recurrence(np.zeros(len(run.cols)), run.bs.mean(0), run.hs, alpha, sigma, zbar, T)
+    assert rel_err(xhat[None], want[None], S, floor=1.0) < tol
+    assert rel_err(xhat[None], OG.worker_mean(last["X"])[None], S, floor=1.0) < tol
+    print(f"\n[{cfg.name} T={T}] tracker identity {worst_track:.2e}, mean iterate {worst_mean:.2e} (of scale)")
+
+
+def test_config4_full_run_single_kernel_step():
+    """n=64, 8x8 torus, d=11,173,962 fp32, K=8, sigma=0.1, lr=0.5, all T=20 steps through detag_step_quadratic,
+    the entry point bench.py times."""
+    cfg = CONFIGS[4]
+    run = _QuadraticRun(cfg, D.Topology.torus(8, 8), tile=256)
+    G = D.new_matrix(run.n, run.d, run.ld, device=DEV)          # g(-1) = 0
+    traj, zbar = run.oracle(cfg.T, cfg.sigma)
+    step = lambda t: run.ctx.step_quadratic(run.X, run.Y, G, run.h, run.b, cfg.lr, cfg.K, sigma=cfg.sigma,
+                                            seed=cfg.seed, step=t)
+    _check_run(run, traj, zbar, cfg.T, cfg.sigma, step, lambda: G, TOL_F32, 2e-6)
+
+
+@pytest.mark.parametrize("path", ["single_kernel", "per_round"])
+def test_config2_full_run(path):
+    """n=16 ring, d=272,474 fp32, K=6, sigma=0.1, lr=0.5, all T=200 steps: gradient query + phase in one
+    kernel, and the gradient kernel followed by one launch per gossip round."""
+    cfg = CONFIGS[2]
+    run = _QuadraticRun(cfg, D.Topology.ring(), tile=256, samples=3000)
+    traj, zbar = run.oracle(cfg.T, cfg.sigma)
+    bufs = [D.new_matrix(run.n, run.d, run.ld, device=DEV) for _ in range(2)]
+    if path == "single_kernel":
+        step = lambda t: run.ctx.step_quadratic(run.X, run.Y, bufs[0], run.h, run.b, cfg.lr, cfg.K,
+                                                sigma=cfg.sigma, seed=cfg.seed, step=t)
+        grad_of = lambda: bufs[0]
+    else:
+        run.ctx.set_path(D.DETAG_PATH_PER_ROUND)
+
+        def step(t):
+            run.ctx.grad_quadratic_diag(run.X, run.h, run.b, bufs[0], sigma=cfg.sigma, seed=cfg.seed, step=t)
+            run.ctx.step(run.X, run.Y, bufs[0], bufs[1], cfg.lr, cfg.K)
+            bufs.reverse()                                       # bufs[1] now holds this step's gradient
+        grad_of = lambda: bufs[1]
+    _check_run(run, traj, zbar, cfg.T, cfg.sigma, step, grad_of, TOL_F32, 2e-6)
+
+
+@pytest.mark.parametrize("path", ["rounds", "dense"])
+def test_config5_full_run(path):
+    """n=256, the library's seeded random 4-regular graph with Metropolis weights, d=1,048,576, bf16 X and Y,
+    K=16, lr=0.5, all T=50 steps at full width: the K rounds on chip, and as one product with the gossip
+    polynomial."""
+    cfg = CONFIGS[5]
+    run = _QuadraticRun(cfg, D.Topology.random_regular(cfg.degree, cfg.seed), tile=64,
+                        state_dtype=torch.bfloat16, samples=500)
+    assert run.ctx.has_fused()
+    if path == "dense":
+        run.ctx.set_path(D.DETAG_PATH_DENSE)
+    traj, zbar = run.oracle(cfg.T, 0.0)
+    bufs = [D.new_matrix(run.n, run.d, run.ld, device=DEV) for _ in range(2)]
+
+    def step(t):
+        run.ctx.grad_quadratic_diag(run.X, run.h, run.b, bufs[0])
+        run.ctx.step(run.X, run.Y, bufs[0], bufs[1], cfg.lr, cfg.K)
+        bufs.reverse()
+    # stored state is bf16: the identities hold up to the rounding of 256 stored values per column
+    _check_run(run, traj, zbar, cfg.T, 0.0, step, lambda: bufs[1], TOL_BF16, 2.0 ** -9)
+
+
+def test_config3_full_run():
+    """n=32 ring, softmax regression on label-sorted shards (3072 features, 10 classes, 1,562 samples per worker,
+    batch 128), K=8, lr=0.01, all T=100 steps at full size; the objective couples the columns, so the oracle
+    follows the whole 32 x 30,730 state."""
+    cfg = CONFIGS[3]
+    n, d, K, alpha, T = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.T
+    F, C, S, B = (cfg.extra[k] for k in ("F", "C", "S", "B"))
+    ld = D.padded_ld(d)
+    feats32, labels = gen.softmax_problem(n, S, F, C, cfg.seed)
+    feats_bf = torch.from_numpy(feats32).to(torch.bfloat16)                 # the stored data
+    feats_ref = feats_bf.to(torch.float32).numpy().astype(np.float64)       # what the oracle sees
+    feats_dev, lab_dev = feats_bf.to(DEV), torch.from_numpy(labels).to(DEV)
+    ctx = D.detag_create(D.Topology.ring(), n, d, ld)
+    W = ctx.dense_W()
+    OT.check_gossip_matrix(W, gen.edges_ring(n))
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    Xd, Yd, Ga, Gb = (D.new_matrix(n, d, ld, device=DEV) for _ in range(4))
+    loss = torch.zeros(n, device=DEV)
+    host = lambda t: t.cpu().numpy()[:, :d].astype(np.float64)
+    X = np.zeros((n, d)); Y = np.zeros((n, d)); Gold = np.zeros((n, d))
+    worst_track = worst_mean = 0.0
+    first_loss = None
+    for t in range(T):
+        idx = gen.batch_indices(n, S, B, seed=cfg.seed, step=t)
+        xbar_prev, ybar_prev = host(Xd).mean(0), host(Yd).mean(0)
+        ctx.grad_softmax_bf16(Xd, feats_dev, lab_dev, torch.from_numpy(idx).to(DEV), C, Ga, loss)
+        ctx.step(Xd, Yd, Ga, Gb, alpha, K)
+        Ga, Gb = Gb, Ga
+        Gnew, lr = OO.grad_softmax(X, feats_ref, labels, idx, F, C)
+        Sin = max(amax(X, Y, Gnew, Gold), np.abs(feats_ref).max() / B)
+        Xn, Yn = OG.detag_step(X, Y, Gnew, Gold, W, alpha, K, eta)
+        torch.cuda.synchronize()
+        Xg, Yg, Gg = host(Xd), host(Yd), host(Gb)
+        worst_track = max(worst_track, np.abs(Yg.mean(0) - Gg.mean(0)).max() / Sin)
+        worst_mean = max(worst_mean, np.abs(Xg.mean(0) - (xbar_prev - alpha * ybar_prev)).max() / Sin)
+        if t == 0:
+            first_loss = float(lr.mean())
+            assert rel_err(Gg, Gnew, Sin) < TOL_F32
+            assert rel_err(Xg, Xn, Sin) < TOL_F32 and rel_err(Yg, Yn, Sin) < TOL_F32
+        X, Y, Gold = Xn, Yn, Gnew
+    assert worst_track < 2e-6 and worst_mean < 2e-6, (worst_track, worst_mean)
+    assert np.abs(loss.cpu().numpy() - lr).max() < 1e-5 * max(1.0, np.abs(lr).max())
+    assert float(lr.mean()) < 0.5 * first_loss                  # and it trains: the batch loss has halved
+    S_ = amax(X, Y, Gold)
+    assert rel_err(Xg, X, S_, floor=1.0) < TOL_F32
+    assert rel_err(Yg, Y, S_, floor=1.0) < TOL_F32
+    xhat = ctx.mean(Xd).cpu().numpy()[:d].astype(np.float64)
+    assert rel_err(xhat[None], OG.worker_mean(X)[None], S_, floor=1.0) < TOL_F32
+    print(f"\n[{cfg.name} T={T}] tracker identity {worst_track:.2e}, mean iterate {worst_mean:.2e} (of scale); "
+          f"batch loss {first_loss:.4f} -> {float(lr.mean()):.4f}")

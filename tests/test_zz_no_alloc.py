@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2006_08085_amd as D
-from gpu_util import DEV, _built, to_dev  # noqa: F401
+from tests.gpu_util import DEV, _built, to_dev  # noqa: F401
 from oracle import gossip as OG
 
 pytestmark = pytest.mark.gpu

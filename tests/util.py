@@ -1,4 +1,6 @@
 """Shared helpers for the parity tests."""
+import os
+
 import numpy as np
 
 # Tolerances of the parity bar: max relative error against the fp64 oracle.
@@ -17,6 +19,28 @@ TOL_BF16 = 2e-2
 FLOOR = 1.0 / 16.0
 
 
+# Every comparison made through rel_err is also measured under tighter floors, so that the margin of the gate is
+# on record: (test id, asserted floor) -> worst figures seen in that test's comparisons under that floor.  tests/conftest.py prints the table at the end of a run.
+MARGINS: dict = {}
+
+
+def _record(err: np.ndarray, ref_abs: np.ndarray, S: float, floor: float, gate: float):
+    test = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
+    rinf = float(ref_abs.max())
+    fig = {
+        "gate": gate,                                                               # what the test asserts on
+        "floor_S/16": float((err / np.maximum(ref_abs, S / 16.0)).max()),
+        "floor_S/64": float((err / np.maximum(ref_abs, S / 64.0)).max()),
+        "floor_1e-3_ref": float((err / np.maximum(ref_abs, 1e-3 * rinf)).max()) if rinf > 0 else 0.0,
+        "normwise_S": float(err.max() / S),
+        "normwise_ref": float(err.max() / rinf) if rinf > 0 else 0.0,
+    }
+    slot = MARGINS.setdefault((test, floor), {"floor": floor, "count": 0})
+    slot["count"] += 1
+    for k, v in fig.items():
+        slot[k] = max(slot.get(k, 0.0), v)
+
+
 def rel_err(got, ref, scale: float = 0.0, floor: float = FLOOR) -> float:
     """max_ij |got - ref| / max(|ref_ij|, floor * S),  S = max(||ref||_inf, scale).
     `scale` is the largest magnitude among the inputs of the operation."""
@@ -25,7 +49,10 @@ def rel_err(got, ref, scale: float = 0.0, floor: float = FLOOR) -> float:
     S = max(float(np.abs(ref).max()), float(scale))
     if S == 0.0:
         return float(np.abs(got).max())
-    return float((np.abs(got - ref) / np.maximum(np.abs(ref), floor * S)).max())
+    err, ref_abs = np.abs(got - ref), np.abs(ref)
+    gate = float((err / np.maximum(ref_abs, floor * S)).max())
+    _record(err, ref_abs, S, floor, gate)
+    return gate
 
 
 def amax(*arrays) -> float:
