@@ -16,8 +16,11 @@
  *     All other pointers are HOST pointers.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All device work is enqueued on it; no entry point synchronises the
- *     host unless its comment says so.  Results written to *_dev outputs are
- *     valid once the stream reaches them.
+ *     host unless its comment says so, with one exception: memory the context
+ *     owns (per-round scratch, gradient scratch, the dense path's polynomial)
+ *     is allocated by the first call that needs it, unless detag_reserve_*
+ *     did so before.  Results written to *_dev outputs are valid once the
+ *     stream reaches them.
  *   - Calls return a detag_status; nothing throws or aborts across the ABI.
  *     detag_last_error() gives the text of the last failure.
  *   - Calls on one context come from one host thread at a time.  Work of two
@@ -166,6 +169,28 @@ int32_t detag_has_fused(const detag_ctx *ctx);
  * eigenvalues mu, so it gives the exact contraction of the K rounds; DETAG_PATH_DENSE multiplies by it.
  */
 detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double eta, double *P_out);
+
+/*
+ * Memory the library owns is allocated on first use: the per-round path's
+ * scratch matrices, the dense path's uploaded polynomial for a (K, eta), the
+ * gradient scratch.  Such a first use allocates, and for the polynomial also
+ * blocks the host.  The two calls below do that work up front, so that every
+ * later call only enqueues kernels; they are what a caller needs before it
+ * records calls into a HIP graph.  While `stream` is being captured, an entry
+ * point that would still have to allocate returns DETAG_EINVAL and enqueues
+ * nothing.
+ *
+ * detag_reserve_gossip: path = DETAG_PATH_PER_ROUND reserves the scratch of
+ *   detag_gossip_accel / detag_step / detag_dpsgd_step / detag_average_consensus
+ *   on that path (K and eta are ignored); path = DETAG_PATH_DENSE evaluates
+ *   and uploads the polynomial for (K, eta) (eta < 0: the context's eta) into
+ *   the context's cache of four.
+ * detag_reserve_gradient: m > 0 reserves for detag_grad_lstsq with that m;
+ *   F, C, B > 0 for detag_grad_softmax_bf16 with those sizes; zeros skip.
+ * Both may allocate and block; call them outside any capture.
+ */
+detag_status detag_reserve_gossip(detag_ctx *ctx, detag_path path, int32_t K, double eta);
+detag_status detag_reserve_gradient(detag_ctx *ctx, int32_t m, int32_t F, int32_t C, int32_t B);
 
 /*
  * Accelerated gossip, Algorithm 3, for all workers at once, in place:

@@ -30,7 +30,7 @@ _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DE
                  "DETAG_EUNSUPPORTED", "DETAG_ENOMEM", "DETAG_EHIP"]
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
-           "detag_get_phase_length", "detag_get_gossip_polynomial", "detag_has_fused", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
+           "detag_get_phase_length", "detag_get_gossip_polynomial", "detag_has_fused", "detag_reserve_gossip", "detag_reserve_gradient", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
            "detag_factors_get_program",
            "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
@@ -81,6 +81,10 @@ def lib() -> C.CDLL:
     L.detag_set_path.restype = C.c_int
     L.detag_has_fused.argtypes = [vp]
     L.detag_has_fused.restype = i32
+    L.detag_reserve_gossip.argtypes = [vp, C.c_int, i32, f64]
+    L.detag_reserve_gossip.restype = C.c_int
+    L.detag_reserve_gradient.argtypes = [vp, i32, i32, i32, i32]
+    L.detag_reserve_gradient.restype = C.c_int
     L.detag_gossip_accel.argtypes = [vp, vp, i32, f64, vp]
     L.detag_gossip_accel.restype = C.c_int
     L.detag_track.argtypes = [vp, vp, vp, vp, vp]
@@ -341,6 +345,12 @@ class Context:
     def has_fused(self) -> bool:
         return bool(lib().detag_has_fused(self._h))
 
+    def reserve_gossip(self, path: int, K: int = 1, eta: float = -1.0):
+        self._check(lib().detag_reserve_gossip(self._h, path, K, eta))
+
+    def reserve_gradient(self, m: int = 0, F: int = 0, C_classes: int = 0, B: int = 0):
+        self._check(lib().detag_reserve_gradient(self._h, m, F, C_classes, B))
+
     # -- hot path ------------------------------------------------------------
     def gossip_accel(self, Z, K: int, eta: float = -1.0):
         self._check(lib().detag_gossip_accel(self._h, self._state(Z, "Z"), K, eta, self._stream()))
@@ -487,6 +497,8 @@ def detag_get_phase_length(ctx: Context, outer_ratio=0.0): return ctx.phase_leng
 def detag_get_gossip_polynomial(ctx: Context, K, eta=-1.0): return ctx.gossip_polynomial(K, eta)
 def detag_set_path(ctx: Context, path: int): ctx.set_path(path)
 def detag_has_fused(ctx: Context): return ctx.has_fused()
+def detag_reserve_gossip(ctx: Context, path, K=1, eta=-1.0): ctx.reserve_gossip(path, K, eta)
+def detag_reserve_gradient(ctx: Context, m=0, F=0, C_classes=0, B=0): ctx.reserve_gradient(m, F, C_classes, B)
 def detag_gossip_accel(ctx: Context, Z, K, eta=-1.0): ctx.gossip_accel(Z, K, eta)
 def detag_track(ctx: Context, Y, G_new, G_old): ctx.track(Y, G_new, G_old)
 def detag_step(ctx: Context, X, Y, G_new, G_old, alpha, K, eta=-1.0, variant=DETAG_VARIANT_ATC):

@@ -37,21 +37,15 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None = None, tag: str = "",
-          csrc: str | None = None) -> str:
-    """extra_flags / out / tag / csrc exist for experiments: a differently configured
-    library (or one from another source directory) written somewhere else, with its
-    own object directory."""
-    CSRC = csrc or globals()["CSRC"]
+def build(verbose: bool = True, jobs: int = 8) -> str:
     hipcc = _hipcc()
-    lib_out = out or LIB
-    bdir = os.path.join(ROOT, "_build") if not tag else os.path.join(ROOT, "_work", "build" + tag)
+    bdir = os.path.join(ROOT, "_build")
     os.makedirs(bdir, exist_ok=True)
-    srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    srcs = list(SOURCES)
 
     def compile_one(src: str) -> str:
         obj = os.path.join(bdir, src + ".o")
-        cmd = [hipcc, *FLAGS, "-I", CSRC, *extra_flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, "-I", CSRC, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                         if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
@@ -63,6 +57,7 @@ def build(verbose: bool = True, jobs: int = 8, extra_flags=(), out: str | None =
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(compile_one, srcs))
+    lib_out = LIB
     tmp = lib_out + ".tmp"
     r = subprocess.run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", tmp, *objs],
                        capture_output=True, text=True)

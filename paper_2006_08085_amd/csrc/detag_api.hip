@@ -77,9 +77,26 @@ detag_status need_device(const detag_ctx *ctx) {
   return DETAG_OK;
 }
 
-detag_status need_scratch(detag_ctx *ctx, int first, int count) {
+// A stream that is being recorded into a HIP graph must see kernel launches only: an allocation, a blocking
+// copy or a device synchronisation would fail or invalidate the recording half-way.
+bool is_capturing(void *stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st != hipStreamCaptureStatusNone;
+}
+
+detag_status refuse_while_capturing(const detag_ctx *ctx, const char *what, const char *reserve) {
+  return set_err(ctx, DETAG_EINVAL, std::string("the stream is being captured and this call would have to allocate ") +
+                                        what + ": call " + reserve + " before the capture begins");
+}
+
+detag_status need_scratch(detag_ctx *ctx, int first, int count, void *stream) {
   for (int k = first; k < first + count; ++k)
     if (!ctx->scratch[k]) {
+      if (is_capturing(stream)) return refuse_while_capturing(ctx, "the per-round gossip scratch", "detag_reserve_gossip");
       hipError_t e = hipMalloc(&ctx->scratch[k], scratch_bytes(ctx->shape));
       if (e != hipSuccess) {
         ctx->scratch[k] = nullptr;
@@ -90,8 +107,9 @@ detag_status need_scratch(detag_ctx *ctx, int first, int count) {
   return DETAG_OK;
 }
 
-detag_status need_grad_scratch(detag_ctx *ctx, int64_t floats) {
+detag_status need_grad_scratch(detag_ctx *ctx, int64_t floats, void *stream) {
   if (ctx->resid_count >= floats) return DETAG_OK;
+  if (is_capturing(stream)) return refuse_while_capturing(ctx, "the gradient scratch", "detag_reserve_gradient");
   (void)hipFree(ctx->d_resid);
   ctx->d_resid = nullptr, ctx->resid_count = 0;
   if (hipMalloc(reinterpret_cast<void **>(&ctx->d_resid), size_t(floats) * sizeof(float)) != hipSuccess) {
@@ -140,11 +158,13 @@ Shape as_f32(Shape s) { return s.bf16 = false, s; }
 
 // The device copy of p_K(W^T) for DETAG_PATH_DENSE: from the context's small cache, or evaluated and uploaded now.
 // A buffer is rewritten only after the device has drained, since an earlier launch may still read it.
-detag_status dense_poly(detag_ctx *ctx, int K, float eta, const uint16_t **frag) {
+detag_status dense_poly(detag_ctx *ctx, int K, float eta, const uint16_t **frag, void *stream) {
   detag_ctx::DensePoly *slot = nullptr;
   for (auto &e : ctx->poly)
     if (e.d_frag && e.K == K && e.eta == eta) slot = &e;
   if (!slot) {
+    if (is_capturing(stream))
+      return refuse_while_capturing(ctx, "and upload the gossip polynomial of this (K, eta)", "detag_reserve_gossip");
     const int terms = dense_poly_terms(ctx->shape.bf16);
     std::vector<uint16_t> host;
     if (!build_dense_poly(ctx->W, K, double(eta), terms, host))
@@ -172,7 +192,7 @@ detag_status dense_poly(detag_ctx *ctx, int K, float eta, const uint16_t **frag)
 detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, void *stream) {
   if (K == 0) return DETAG_OK;
   const int nscratch = (K % 2 == 1 && K >= 3) ? 2 : 1;
-  if (detag_status st = need_scratch(ctx, 0, nscratch)) return st;
+  if (detag_status st = need_scratch(ctx, 0, nscratch, stream)) return st;
   void *B = ctx->scratch[0], *C = ctx->scratch[1];
   const Shape s = as_f32(ctx->shape);
   const DevCsr w = dev_csr(ctx);
@@ -211,7 +231,7 @@ struct WideState {
     user[0] = a, user[1] = b;
     work[0] = a, work[1] = b;
     if (!ctx->shape.bf16) return DETAG_OK;
-    if (detag_status st = need_scratch(ctx, 2, b ? 2 : 1)) return st;
+    if (detag_status st = need_scratch(ctx, 2, b ? 2 : 1, stream)) return st;
     for (int k = 0; k < 2 && user[k]; ++k) {
       work[k] = ctx->scratch[2 + k];
       if (int rc = launch_widen(ctx->shape, user[k], static_cast<float *>(work[k]), stream))
@@ -392,6 +412,29 @@ detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double
   return DETAG_OK;
 }
 
+detag_status detag_reserve_gossip(detag_ctx *ctx, detag_path path, int32_t K, double eta) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_DENSE)
+    return set_err(ctx, DETAG_EINVAL, "only DETAG_PATH_PER_ROUND and DETAG_PATH_DENSE own memory to reserve");
+  if (path == DETAG_PATH_PER_ROUND)  // z_r buffers, and the widened copies of bf16 X and Y
+    return need_scratch(ctx, 0, ctx->shape.bf16 ? 4 : 2, nullptr);
+  if (ctx->W.n > 256) return set_err(ctx, DETAG_EUNSUPPORTED, "the dense path needs n <= 256");
+  if (K < 1) return set_err(ctx, DETAG_EINVAL, "K must be >= 1");
+  float e;
+  if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
+  const uint16_t *frag = nullptr;
+  return dense_poly(ctx, K, e, &frag, nullptr);
+}
+
+detag_status detag_reserve_gradient(detag_ctx *ctx, int32_t m, int32_t F, int32_t C, int32_t B) {
+  if (detag_status st = need_device(ctx)) return st;
+  if (m < 0 || F < 0 || C < 0 || B < 0) return set_err(ctx, DETAG_EINVAL, "sizes must be >= 0");
+  int64_t floats = int64_t(ctx->shape.n) * m;
+  if (F > 0 && C > 0 && B > 0) floats = std::max(floats, softmax_scratch_floats(ctx->shape.n, C, B, F));
+  if (floats == 0) return DETAG_OK;
+  return need_grad_scratch(ctx, floats, nullptr);
+}
+
 detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double eta, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, Z_dev, "Z_dev")) return st;
@@ -411,7 +454,7 @@ detag_status detag_gossip_accel(detag_ctx *ctx, void *Z_dev, int32_t K, double e
       break;
     case kDense: {
       const uint16_t *frag = nullptr;
-      if (detag_status st = dense_poly(ctx, K, e, &frag)) return st;
+      if (detag_status st = dense_poly(ctx, K, e, &frag, stream)) return st;
       rc = launch_dense_phase(ctx->shape, 0, Z_dev, nullptr, nullptr, nullptr, 0.f, frag, stream);
       break;
     }
@@ -469,7 +512,7 @@ detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *G
   }
   if (path == kDense) {
     const uint16_t *frag = nullptr;
-    if (detag_status st = dense_poly(ctx, K, e, &frag)) return st;
+    if (detag_status st = dense_poly(ctx, K, e, &frag, stream)) return st;
     const int rc = launch_dense_phase(s, mode, X_dev, Y_dev, Gnew_dev, Gold_dev, a, frag, stream);
     return rc ? hip_fail(ctx, "dense phase", rc) : DETAG_OK;
   }
@@ -500,7 +543,7 @@ detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, d
                                            stream);
     return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
   }
-  if (detag_status st = need_scratch(ctx, 0, 1)) return st;
+  if (detag_status st = need_scratch(ctx, 0, 1, stream)) return st;
   int rc = launch_copy_state(ctx->shape, X_dev, ctx->scratch[0], stream);
   if (!rc) rc = launch_dpsgd(ctx->shape, dev_csr(ctx), ctx->scratch[0], X_dev, G_dev, float(alpha), stream);
   return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
@@ -667,7 +710,7 @@ detag_status detag_average_consensus(detag_ctx *ctx, const detag_factors *f, voi
     // rc < 0: does not fit the LDS of a block here; fall through to one launch per factor
   }
   // one launch per factor, between Z and a scratch matrix
-  if (detag_status st = need_scratch(ctx, 0, 1)) return st;
+  if (detag_status st = need_scratch(ctx, 0, 1, stream)) return st;
   void *cur = Z_dev, *other = ctx->scratch[0];
   for (int r = 0; r < R; ++r) {
     DevCsr a;
@@ -775,7 +818,7 @@ detag_status detag_grad_lstsq(detag_ctx *ctx, const void *X_dev, const float *A_
   if (detag_status st = check_f32_ptr(ctx, b_dev, "b_dev")) return st;
   if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
   if (m < 1) return set_err(ctx, DETAG_EINVAL, "m must be >= 1");
-  if (detag_status st = need_grad_scratch(ctx, int64_t(ctx->shape.n) * m)) return st;
+  if (detag_status st = need_grad_scratch(ctx, int64_t(ctx->shape.n) * m, stream)) return st;
   const int rc = launch_grad_lstsq(ctx->shape, X_dev, A_dev, b_dev, m, ctx->d_resid, G_dev, stream);
   return rc ? hip_fail(ctx, "least-squares gradient", rc) : DETAG_OK;
 }
@@ -795,7 +838,7 @@ detag_status detag_grad_softmax_bf16(detag_ctx *ctx, const void *X_dev, const ui
     return set_err(ctx, DETAG_EUNSUPPORTED, "softmax gradient limits: 2 <= C <= 10, F % 32 == 0, B % 32 == 0, B <= 256");
   if (int64_t(C) * F + C != ctx->shape.d)
     return set_err(ctx, DETAG_EINVAL, "d must equal C*F + C");
-  if (detag_status st = need_grad_scratch(ctx, softmax_scratch_floats(ctx->shape.n, C, B, F))) return st;
+  if (detag_status st = need_grad_scratch(ctx, softmax_scratch_floats(ctx->shape.n, C, B, F), stream)) return st;
   const int rc = launch_grad_softmax(ctx->shape, X_dev, feat_dev, labels_dev, batch_dev, S, F, C, B, ctx->d_resid,
                                      G_dev, loss_dev, stream);
   return rc ? hip_fail(ctx, "softmax gradient", rc) : DETAG_OK;

@@ -57,22 +57,17 @@ __device__ __forceinline__ rsrc_t row_of(const E *base, int64_t tile, int64_t ld
 // Cache-policy bits of the buffer instructions on gfx950 (the `aux` operand):
 // bit 0 = sc0, bit 1 = nt, bit 4 = sc1.  State tiles are touched exactly once
 // per kernel, so they are streamed with nt (non-temporal).
-#ifndef DETAG_AUX_LOAD
-#define DETAG_AUX_LOAD 2
-#endif
-#ifndef DETAG_AUX_STORE
-#define DETAG_AUX_STORE 2
-#endif
+constexpr int kAuxLoad = 2, kAuxStore = 2;
 
 template <typename ST>
 __device__ __forceinline__ float buf_load(rsrc_t r, uint32_t byte_off);
 template <>
 __device__ __forceinline__ float buf_load<float>(rsrc_t r, uint32_t byte_off) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, int(byte_off), 0, DETAG_AUX_LOAD));
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, int(byte_off), 0, kAuxLoad));
 }
 template <>
 __device__ __forceinline__ float buf_load<bf16_t>(rsrc_t r, uint32_t byte_off) {
-  const uint16_t h = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(r, int(byte_off), 0, DETAG_AUX_LOAD));
+  const uint16_t h = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(r, int(byte_off), 0, kAuxLoad));
   return __uint_as_float(uint32_t(h) << 16);
 }
 
@@ -80,11 +75,11 @@ template <typename ST>
 __device__ __forceinline__ void buf_store(rsrc_t r, uint32_t byte_off, float v);
 template <>
 __device__ __forceinline__ void buf_store<float>(rsrc_t r, uint32_t byte_off, float v) {
-  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), r, int(byte_off), 0, DETAG_AUX_STORE);
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), r, int(byte_off), 0, kAuxStore);
 }
 template <>
 __device__ __forceinline__ void buf_store<bf16_t>(rsrc_t r, uint32_t byte_off, float v) {
-  __builtin_amdgcn_raw_buffer_store_b16(short(bf16_bits_rne(v)), r, int(byte_off), 0, DETAG_AUX_STORE);
+  __builtin_amdgcn_raw_buffer_store_b16(short(bf16_bits_rne(v)), r, int(byte_off), 0, kAuxStore);
 }
 
 // Hides a uniform pointer's value from the optimiser (it stays in scalar

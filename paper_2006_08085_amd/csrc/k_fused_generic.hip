@@ -11,8 +11,8 @@
 // in pairs, the weights), read once per kernel, and every LDS access is 64
 // consecutive words, free of bank conflicts.  One round = read the neighbours
 // from LDS, barrier, write the new values back, barrier.  HBM sees the state
-// once per phase (the ATC phase reads Y twice: 18 B instead of 16 B per element
-// with bf16 state); the rounds run at the LDS bandwidth, (deg+1) LDS words per
+// once per phase (16 B per element with bf16 state, 24 B with fp32); the rounds
+// run at the LDS bandwidth, (deg+1) LDS words per
 // output per round.  The kernel is kept within 64 VGPRs so that two blocks
 // share a compute unit (2 x 64 KiB of LDS): one block's loads and stores then
 // run under the other's rounds.
@@ -143,35 +143,33 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
 #pragma unroll
     for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
   } else if constexpr (MODE == 1) {
+    // every input is read once: the second gossip's input Y + Gn - Go waits in registers under the first
+    float v0[kRpt];
 #pragma unroll
     for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
-      float x[kBatch], y[kBatch];
+      float x[kBatch], y[kBatch], gn[kBatch], go[kBatch];
 #pragma unroll
       for (int q = 0; q < kBatch; ++q) {
         x[q] = buf_load<ST>(win(X, tile, ld, row(r0 + q), n, valid), so);
-        y[q] = buf_load<ST>(win(Y, tile, ld, row(r0 + q), n, valid), so);
-      }
-#pragma unroll
-      for (int q = 0; q < kBatch; ++q) cur[r0 + q] = fmaf(-alpha, y[q], x[q]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
-#pragma unroll
-    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
-      float y[kBatch], gn[kBatch], go[kBatch];
-#pragma unroll
-      for (int q = 0; q < kBatch; ++q) {
         y[q] = buf_load<ST>(win(Y, tile, ld, row(r0 + q), n, valid), so);
         gn[q] = buf_load<float>(win(Gn, tile, ld, row(r0 + q), n, valid), fo);
         go[q] = buf_load<float>(win(Go, tile, ld, row(r0 + q), n, valid), fo);
       }
 #pragma unroll
-      for (int q = 0; q < kBatch; ++q) cur[r0 + q] = y[q] + gn[q] - go[q];
+      for (int q = 0; q < kBatch; ++q) {
+        cur[r0 + q] = fmaf(-alpha, y[q], x[q]);
+        v0[r0 + q] = y[q] + gn[q] - go[q];
+        pin_vgpr(v0[r0 + q]);  // the sum now, not its three operands carried through the rounds
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
+    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+#pragma unroll
+    for (int r = 0; r < kRpt; ++r) {
+      buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
+      cur[r] = v0[r];
+    }
+    __builtin_amdgcn_sched_barrier(0);
     gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
     for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so, cur[r]);

@@ -217,3 +217,72 @@ def test_odd_pitch_takes_the_scalar_paths(dtype):
     assert rel_err(to_host(Zd, d), held - 0.25 * Gk, amax(held, Gk)) < tol
     assert np.array_equal(to_host(Od, d), to_host(Zd, d)) and np.all(to_host(Gd, d) == 0.0)
     assert padding_ok(Zd, d) and padding_ok(Gd, d)
+
+
+def test_capture_refuses_to_allocate_and_works_after_reserve():
+    """Under HIP graph capture an entry point that would have to allocate its scratch returns a status and
+    enqueues nothing; after detag_reserve_* the same calls record, and the replayed graph (three times, with
+    eager work in between) gives the bits of the eager calls."""
+    n, d, ld, K = 8, 700, 704, 3
+    ctx, W = make_ctx("ring", n, d, ld)
+    ctx.set_path(D.DETAG_PATH_PER_ROUND)
+    Z = gen.state(n, d, seed=5)
+    m = 16
+    A = torch.from_numpy(gen.lstsq_problem(n, m, d, seed=1, shift=0.0)[0]).to(DEV)
+    bb = torch.from_numpy(gen.lstsq_problem(n, m, d, seed=1, shift=0.0)[1]).to(DEV)
+    Zd, Gd = to_dev(Z, ld), D.new_matrix(n, d, ld)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            with pytest.raises(D.DetagError) as e1:
+                ctx.gossip_accel(Zd, K)                          # per-round scratch does not exist yet
+            with pytest.raises(D.DetagError) as e2:
+                ctx.grad_lstsq(Zd, A, bb, Gd)                    # nor the residual scratch
+            Gd.zero_()                                           # so that the recording holds some node
+    assert e1.value.status == D.DETAG_EINVAL and "detag_reserve_gossip" in e1.value.message
+    assert e2.value.status == D.DETAG_EINVAL and "detag_reserve_gradient" in e2.value.message
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(Zd, d), Z.astype(np.float64))  # nothing ran
+    ctx.reserve_gossip(D.DETAG_PATH_PER_ROUND)
+    ctx.reserve_gradient(m=m)
+    with pytest.raises(D.DetagError):
+        ctx.reserve_gossip(D.DETAG_PATH_FUSED)                   # owns nothing to reserve
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph2, stream=side):
+            ctx.gossip_accel(Zd, K)
+            ctx.grad_lstsq(Zd, A, bb, Gd)
+    Ze, Ge = to_dev(Z, ld), D.new_matrix(n, d, ld)
+    for rep in range(3):
+        graph2.replay()
+        ctx.gossip_accel(Ze, K)
+        ctx.grad_lstsq(Ze, A, bb, Ge)
+        torch.cuda.synchronize()
+        assert np.isfinite(torch.randn(100, device=DEV).sum().item())
+        assert torch.equal(Zd, Ze) and torch.equal(Gd, Ge), rep
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    ref = Z
+    for _ in range(3):
+        ref = OG.accelerated_gossip(ref, W, K, eta)
+    assert rel_err(to_host(Zd, d), ref, amax(Z), floor=1.0) < TOL_F32
+    # the dense path: the polynomial of an unseen (K, eta) is refused under capture, accepted once reserved
+    ctx.set_path(D.DETAG_PATH_DENSE)
+    graph3 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph3, stream=side):
+            with pytest.raises(D.DetagError) as e3:
+                ctx.gossip_accel(Zd, 5)
+            Gd.zero_()
+    assert "detag_reserve_gossip" in e3.value.message
+    ctx.reserve_gossip(D.DETAG_PATH_DENSE, 5)
+    Z1, Z2 = to_dev(Z, ld), to_dev(Z, ld)
+    graph4 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph4, stream=side):
+            ctx.gossip_accel(Z1, 5)
+    graph4.replay()
+    ctx.gossip_accel(Z2, 5)
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z2)

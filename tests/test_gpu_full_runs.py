@@ -97,7 +97,10 @@ class _QuadraticRun:
         return traj, zbar
 
 
-def _check_run(run, traj, zbar, T, sigma, do_step, gradient_of, tol, inv_tol):
+TIGHT = 1.0 / 64.0      # entry-by-entry floor of these tests: S/64 instead of the suite's S/16 (measured margin: 3x or more)
+
+
+def _check_run(run, traj, zbar, T, sigma, do_step, gradient_of, tol, inv_tol, final_floor=1.0):
     """Drive T device steps; after each: the two identities on the device state (sampled columns); after the
     first: entry by entry; at T: normwise, the worker mean against the scalar recurrence."""
     cfg, alpha = run.cfg, run.cfg.lr
@@ -111,15 +114,15 @@ def _check_run(run, traj, zbar, T, sigma, do_step, gradient_of, tol, inv_tol):
         worst_mean = max(worst_mean, np.abs(Xg.mean(0) - (xbar_prev - alpha * ybar_prev)).max() / S)
         xbar_prev, ybar_prev = Xg.mean(0), Yg.mean(0)
         if t == 0:                                               # one step from identical inputs: entry by entry
-            assert rel_err(Gg, traj[0]["G"], S) < TOL_F32
-            assert rel_err(Xg, traj[0]["raw"][0], S) < tol
-            assert rel_err(Yg, traj[0]["raw"][1], S) < tol
+            assert rel_err(Gg, traj[0]["G"], S, floor=TIGHT) < TOL_F32
+            assert rel_err(Xg, traj[0]["raw"][0], S, floor=TIGHT) < tol
+            assert rel_err(Yg, traj[0]["raw"][1], S, floor=TIGHT) < tol
     assert worst_track < inv_tol, f"tracker identity off by {worst_track:.3e} of the state's scale"
     assert worst_mean < inv_tol, f"mean-iterate identity off by {worst_mean:.3e} of the state's scale"
     last = traj[T - 1]
     S = amax(last["X"], last["Y"], last["G"])
-    assert rel_err(Xg, last["X"], S, floor=1.0) < tol
-    assert rel_err(Yg, last["Y"], S, floor=1.0) < tol
+    assert rel_err(Xg, last["X"], S, floor=final_floor) < tol
+    assert rel_err(Yg, last["Y"], S, floor=final_floor) < tol
     # the output of Algorithm 2 (full width on the device) against the topology-free recurrence
     xhat = run.ctx.mean(run.X)[run.idx].double().cpu().numpy()
     want = _recurrence(np.zeros(len(run.cols)), run.bs.mean(0), run.hs, alpha, sigma, zbar, T)
@@ -137,7 +140,8 @@ def test_config4_full_run_single_kernel_step():
     traj, zbar = run.oracle(cfg.T, cfg.sigma)
     step = lambda t: run.ctx.step_quadratic(run.X, run.Y, G, run.h, run.b, cfg.lr, cfg.K, sigma=cfg.sigma,
                                             seed=cfg.seed, step=t)
-    _check_run(run, traj, zbar, cfg.T, cfg.sigma, step, lambda: G, TOL_F32, 2e-6)
+    # the benchmark workload is held entry by entry at the end of its run as well
+    _check_run(run, traj, zbar, cfg.T, cfg.sigma, step, lambda: G, TOL_F32, 2e-6, final_floor=TIGHT)
 
 
 @pytest.mark.parametrize("path", ["single_kernel", "per_round"])
@@ -222,8 +226,8 @@ def test_config3_full_run():
         worst_mean = max(worst_mean, np.abs(Xg.mean(0) - (xbar_prev - alpha * ybar_prev)).max() / Sin)
         if t == 0:
             first_loss = float(lr.mean())
-            assert rel_err(Gg, Gnew, Sin) < TOL_F32
-            assert rel_err(Xg, Xn, Sin) < TOL_F32 and rel_err(Yg, Yn, Sin) < TOL_F32
+            assert rel_err(Gg, Gnew, Sin, floor=TIGHT) < TOL_F32
+            assert rel_err(Xg, Xn, Sin, floor=TIGHT) < TOL_F32 and rel_err(Yg, Yn, Sin, floor=TIGHT) < TOL_F32
         X, Y, Gold = Xn, Yn, Gnew
     assert worst_track < 2e-6 and worst_mean < 2e-6, (worst_track, worst_mean)
     assert np.abs(loss.cpu().numpy() - lr).max() < 1e-5 * max(1.0, np.abs(lr).max())

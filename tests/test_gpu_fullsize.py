@@ -18,6 +18,7 @@ from workloads import CONFIGS, generate as gen
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+TIGHT = 1.0 / 64.0      # entry-by-entry floor at the full sizes: S/64 instead of the suite's S/16 (measured margin: 5x or more)
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -73,12 +74,12 @@ def test_config4_full_size_sampled_columns():
             S1 = amax(Xs, Ys, Gns, Gos)
             torch.cuda.synchronize()
             G_dev = take(Gb)                                    # after the swap Gb holds this step's gradient
-            assert rel_err(G_dev, Gns, S1) < TOL_F32
+            assert rel_err(G_dev, Gns, S1, floor=TIGHT) < TOL_F32
         Xs, Ys = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
         Gos = Gns
         if t == 0:                                              # one step from identical inputs: entry by entry
-            assert rel_err(take(X), Xs, S1) < TOL_F32
-            assert rel_err(take(Y), Ys, S1) < TOL_F32
+            assert rel_err(take(X), Xs, S1, floor=TIGHT) < TOL_F32
+            assert rel_err(take(Y), Ys, S1, floor=TIGHT) < TOL_F32
     S = amax(Xs, Ys, Gos)                                       # end of the short run: normwise
     assert rel_err(take(X), Xs, S, floor=1.0) < TOL_F32
     assert rel_err(take(Y), Ys, S, floor=1.0) < TOL_F32
@@ -117,9 +118,9 @@ def test_config4_full_size_single_kernel_step():
     Gns = OO.grad_quadratic_diag(Xs, hs, bs, ON.normal_noise(seed, step, n, cols), sigma)
     Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
     S = amax(Xs, Ys, Gns, Gos)
-    assert rel_err(take(G), Gns, S) < TOL_F32
-    assert rel_err(take(X), Xr, S) < TOL_F32
-    assert rel_err(take(Y), Yr, S) < TOL_F32
+    assert rel_err(take(G), Gns, S, floor=TIGHT) < TOL_F32
+    assert rel_err(take(X), Xr, S, floor=TIGHT) < TOL_F32
+    assert rel_err(take(Y), Yr, S, floor=TIGHT) < TOL_F32
     Gnew2 = D.new_matrix(n, d, ld, device=dev)
     ctx.grad_quadratic_diag(X2, h, b, Gnew2, sigma=sigma, seed=seed, step=step)
     ctx.step(X2, Y2, Gnew2, Gold2, alpha, K)
@@ -193,7 +194,7 @@ def test_config5_full_size_sampled_columns(path):
     Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
     S = amax(Xs, Ys, Gns, Gos)
     from tests.util import TOL_BF16
-    assert rel_err(take(X), Xr, S) < TOL_BF16
-    assert rel_err(take(Y), Yr, S) < TOL_BF16
+    assert rel_err(take(X), Xr, S, floor=TIGHT) < TOL_BF16
+    assert rel_err(take(Y), Yr, S, floor=TIGHT) < TOL_BF16
     # fp32 on chip, rounded once: within half a bf16 ulp of the oracle wherever the value is not tiny
     assert rel_err(take(X), Xr) < 2.0 ** -8 and rel_err(take(Y), Yr) < 2.0 ** -8
