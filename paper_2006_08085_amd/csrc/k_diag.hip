@@ -1,7 +1,8 @@
 // Diagnostics: the worker mean (the output line of Algorithm 2) and the
 // consensus distance ||X - 1 xbar^T||_F^2 bounded in the proof of Theorem 3.
-// One lane owns one column and walks the n rows; sums are kept in fp64 so the
-// distance stays meaningful when the workers almost agree.  Reductions use a
+// One lane owns one column and walks the n rows once; sums are kept in fp64 and
+// taken relative to the first worker's value, so the distance stays meaningful
+// when the workers almost agree.  Reductions use a
 // fixed order (wavefront shuffle tree, then one block over the per-block
 // partials): results are bit-reproducible.
 #include "dev_common.hpp"
@@ -42,15 +43,20 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(int n, int6
   const int64_t c = int64_t(blockIdx.x) * kThreads + threadIdx.x;
   double acc = 0.0;
   if (c < d) {
-    double s = 0.0;
+    // One pass: with e_i = x_i - x_0 (exact in fp64 for fp32 or bf16 inputs),
+    //   sum_i (x_i - mean)^2 = sum_i e_i^2 - (sum_i e_i)^2 / n.
+    // Both terms are of the size of the result (the shift by x_0 removes the common part of the column), so the
+    // subtraction does not cancel, however close the workers are to agreement.
+    const double x0 = double(to_f32(X[c]));
+    double s1 = 0.0, s2 = 0.0;
 #pragma unroll 16
-    for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));
-    const double m = s / n;
-#pragma unroll 16
-    for (int i = 0; i < n; ++i) {
-      const double dev = double(to_f32(X[int64_t(i) * ld + c])) - m;
-      acc += dev * dev;
+    for (int i = 1; i < n; ++i) {
+      const double e = double(to_f32(X[int64_t(i) * ld + c])) - x0;
+      s1 += e;
+      s2 = fma(e, e, s2);
     }
+    acc = s2 - s1 * s1 / n;
+    acc = acc < 0.0 ? 0.0 : acc;
   }
   const double t = block_sum(acc);
   if (threadIdx.x == 0) partials[blockIdx.x] = t;

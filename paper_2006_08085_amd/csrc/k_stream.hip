@@ -105,6 +105,69 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d
   }
 }
 
+// The same round with the neighbour tile staged in LDS, for n <= kTileRowsMax workers.  A block of four
+// wavefronts owns 64 columns and all n rows of them: row i of z_r is loaded once (wavefront i mod 4, 256
+// contiguous bytes), parked in LDS as fp32, and after one barrier every output row takes its neighbours from
+// there.  HBM sees z_r once, z_{r-1} (or G) once and the output once: 12 bytes per element, where the kernel
+// above re-fetches every row once per neighbour that reads it.  Row indices are uniform in a wavefront, so the
+// CSR row (pointers, columns, weights) is read with scalar loads.  Every access goes through a buffer resource:
+// the ragged last tile and odd pitches need no separate path.
+constexpr int kTileCols = 64, kTileWaves = 4, kTileThreads = 64 * kTileWaves, kTileRowsMax = 256, kTileBatch = 4;
+
+template <typename ST, bool HAS_G>
+__global__ __launch_bounds__(kTileThreads) void gossip_round_tile_kernel(int n, int64_t d, int64_t ld,
+                                                                         const int32_t *__restrict__ rowptr,
+                                                                         const int32_t *__restrict__ colidx,
+                                                                         const float *__restrict__ vals,
+                                                                         const ST *__restrict__ cur, const ST *prev,
+                                                                         ST *out, const float *__restrict__ G,
+                                                                         float c_mix, float eta, float alpha) {
+  extern __shared__ float tile_lds[];  // n x 64
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int64_t tile = int64_t(blockIdx.x) * kTileCols;
+  const uint32_t valid = uint32_t(d - tile < kTileCols ? d - tile : kTileCols);
+  const uint32_t so = lane * uint32_t(sizeof(ST)), fo = lane * 4u;
+  for (int i0 = w; i0 < n; i0 += kTileWaves * kTileBatch) {
+    float z[kTileBatch];
+#pragma unroll
+    for (int q = 0; q < kTileBatch; ++q) {
+      const int i = i0 + q * kTileWaves;
+      z[q] = buf_load<ST>(row_of(cur, tile, ld, i < n ? i : 0, i < n ? valid : 0u), so);
+    }
+#pragma unroll
+    for (int q = 0; q < kTileBatch; ++q) {
+      const int i = i0 + q * kTileWaves;
+      if (i < n) tile_lds[i * kTileCols + lane] = z[q];
+    }
+  }
+  __syncthreads();
+  for (int i0 = w; i0 < n; i0 += kTileWaves * kTileBatch) {
+    float other[kTileBatch];  // z_{r-1} (or the gradient) of this batch of rows, requested before the sums
+#pragma unroll
+    for (int q = 0; q < kTileBatch; ++q) {
+      const int i = i0 + q * kTileWaves;
+      if constexpr (HAS_G) other[q] = buf_load<float>(row_of(G, tile, ld, i < n ? i : 0, i < n ? valid : 0u), fo);
+      else other[q] = buf_load<ST>(row_of(prev, tile, ld, i < n ? i : 0, i < n ? valid : 0u), so);
+    }
+#pragma unroll
+    for (int q = 0; q < kTileBatch; ++q) {
+      const int i = i0 + q * kTileWaves;
+      if (i >= n) break;
+      const float own = tile_lds[i * kTileCols + lane];
+      float acc = 0.f;
+      const int k1 = rowptr[i + 1];
+      for (int k = rowptr[i]; k < k1; ++k) {
+        const int j = colidx[k];
+        acc = fmaf(vals[k], tile_lds[j * kTileCols + lane] - own, acc);  // j == i adds an exact zero
+      }
+      float o;
+      if constexpr (HAS_G) o = own + fmaf(-alpha, other[q], c_mix * acc);
+      else o = own + fmaf(c_mix, acc, eta * (own - other[q]));
+      buf_store<ST>(row_of(out, tile, ld, i, valid), so, o);
+    }
+  }
+}
+
 // mode 0: Y += Gn - Go.   mode 1: X -= alpha*Y (Y before the update); Y += Gn - Go.
 template <typename ST, int VEC, int MODE>
 __global__ __launch_bounds__(kThreads) void elementwise_kernel(int64_t d, int64_t ld, ST *X, ST *Y,
@@ -256,12 +319,21 @@ int rows_per_group_for(const Shape &s, int col_blocks) {
 template <typename ST, bool HAS_G>
 int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, const float *G,
                    float c_mix, float eta, float alpha, void *stream) {
+  auto st = static_cast<hipStream_t>(stream);
+  // narrow matrices (fewer column tiles than compute units) keep the form below, which also splits the rows over blocks
+  if (s.n <= kTileRowsMax && s.d >= int64_t(kTileCols) * 256) {
+    const dim3 tgrid(ceil_div_i64(s.d, kTileCols));
+    const size_t lds_bytes = size_t(s.n) * kTileCols * sizeof(float);
+    gossip_round_tile_kernel<ST, HAS_G><<<tgrid, kTileThreads, lds_bytes, st>>>(
+        s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
+        static_cast<ST *>(out), G, c_mix, eta, alpha);
+    return hip_rc(hipGetLastError());
+  }
   const bool vec = vec_ok(s, {cur, prev, out}, {G});
   const int per_block = kThreads * (vec ? 4 : 1);
   const int col_blocks = ceil_div_i64(s.d, per_block);
   const int rpg = rows_per_group_for(s, col_blocks);
   dim3 grid(col_blocks, (s.n + rpg - 1) / rpg);
-  auto st = static_cast<hipStream_t>(stream);
   if (vec)
     gossip_round_kernel<ST, 4, HAS_G><<<grid, kThreads, 0, st>>>(
         s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),

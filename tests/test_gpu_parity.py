@@ -497,3 +497,49 @@ def test_step_quadratic_unsupported_cases_are_statuses():
     with pytest.raises(D.DetagError) as ei:
         ctx2.step_quadratic(X, X, Gm, h, b, 0.1, 2)
     assert ei.value.status == D.DETAG_EINVAL
+
+
+# ---------------------------------------------------------------------------
+# one gossip round with the neighbour tile staged in LDS (n <= 256, at least 256 column tiles)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,graph", [(5, "asym"), (17, "ring"), (61, "irregular"), (64, "torus88"), (256, "rr")])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("pad", [0, 5])          # pitch a multiple of 64, and an odd pitch
+def test_one_round_with_lds_staged_tile(n, graph, dtype, pad):
+    d = 64 * 256 + 37                            # 257 column tiles, the last one ragged
+    ld = D.padded_ld(d) + pad
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    if graph == "asym":
+        W = 0.5 * np.eye(n) + 0.5 * np.roll(np.eye(n), 1, axis=1)
+        topo = D.Topology.from_dense(W)
+    elif graph == "ring":
+        topo, W = D.Topology.ring(), OT.mixing_matrix(n, gen.edges_ring(n))
+    elif graph == "torus88":
+        topo, W = D.Topology.torus(8, 8), OT.mixing_matrix(n, gen.edges_torus(8, 8))
+    else:
+        e = gen.edges_random_regular(n, 4, seed=n) if graph == "rr" else _irregular_edges(n, seed=n)
+        topo, W = D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), OT.mixing_matrix(n, e, "metropolis")
+    ctx = D.detag_create(topo, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    rnd = OO.round_bf16 if bf else (lambda a: a)
+    cur, prev, G = rnd(gen.state(n, d, 1)), rnd(gen.state(n, d, 2)), gen.state(n, d, 3)
+    eta, alpha = 0.3, 0.05
+    want = (1 + eta) * (W.T @ cur.astype(np.float64)) - eta * prev.astype(np.float64)
+    # out distinct from both inputs, and out written over z_{r-1}
+    cd, pd, od = to_dev(cur, ld, tdt), to_dev(prev, ld, tdt), to_dev(np.zeros((n, d)), ld, tdt)
+    ctx.gossip_round(cd, pd, od, eta)
+    assert rel_err(to_host(od, d), want, amax(cur, prev)) < tol and padding_ok(od, d)
+    ctx.gossip_round(cd, pd, pd, eta)
+    torch.cuda.synchronize()
+    assert torch.equal(pd, od) and padding_ok(pd, d)
+    assert np.array_equal(to_host(cd, d), cur.astype(np.float64))          # z_r is only read
+    # the D-PSGD step on the per-round path takes the same kernel with the gradient in place of z_{r-1}
+    ctx.set_path(D.DETAG_PATH_PER_ROUND)
+    xd, gd = to_dev(cur, ld, tdt), to_dev(G, ld)
+    ctx.dpsgd_step(xd, gd, alpha)
+    assert rel_err(to_host(xd, d), OG.dpsgd_step(cur, G, W, alpha), amax(cur, G)) < tol and padding_ok(xd, d)
+    # K rounds through the per-round path land where the on-chip kernels land
+    K = 3
+    zd = to_dev(cur, ld, tdt)
+    ctx.gossip_accel(zd, K, eta)
+    assert rel_err(to_host(zd, d), OG.accelerated_gossip(cur, W, K, eta), amax(cur)) < tol and padding_ok(zd, d)
