@@ -21,6 +21,9 @@
  *     is allocated by the first call that needs it, unless detag_reserve_*
  *     did so before.  Results written to *_dev outputs are valid once the
  *     stream reaches them.
+ *   - Enumerated arguments cross the ABI as int32_t (the enum types below name
+ *     their values): a value outside the enumeration is an ordinary bad
+ *     argument, answered with DETAG_EINVAL.
  *   - Calls return a detag_status; nothing throws or aborts across the ABI.
  *     detag_last_error() gives the text of the last failure.
  *   - Calls on one context come from one host thread at a time.  Work of two
@@ -132,7 +135,7 @@ typedef enum {
  * On failure *out is NULL and detag_last_error(NULL) has the reason.
  */
 detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int64_t ld,
-                          detag_dtype state, detag_ctx **out);
+                          int32_t state /* detag_dtype */, detag_ctx **out);
 
 /* Frees the context and its device scratch.  Synchronises the device. NULL is ignored. */
 void detag_destroy(detag_ctx *ctx);
@@ -157,7 +160,38 @@ detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const
 
 /* Select the gossip kernels (default AUTO).  FUSED is refused with EUNSUPPORTED
  * if the context's n has no on-chip kernel. */
-detag_status detag_set_path(detag_ctx *ctx, detag_path path);
+detag_status detag_set_path(detag_ctx *ctx, int32_t path /* detag_path */);
+
+/*
+ * Which kernel family detag_gossip_accel and detag_step (K >= 1) run on this
+ * context with its current path: it depends on the topology and on n, and the
+ * families differ in cost by integer factors, so a caller sizing a run should
+ * look.  Measured on MI355X, fp32 state unless noted:
+ *   DETAG_KERNEL_REGISTER_TILE  ring with n in {4, 8, 16, 32, 64}, torus 4x4,
+ *     4x8, 8x8 (built from DETAG_TOPO_RING / DETAG_TOPO_TORUS2D with uniform
+ *     weights and any kappa).  All n rows of a column in registers, K rounds
+ *     on chip: 24 B per element and phase whatever K is, 0.66 of HBM peak at
+ *     n = 64, d = 11.2 M.  Only this family serves detag_step_quadratic and
+ *     the one-pass detag_dpsgd_step.
+ *   DETAG_KERNEL_LDS_TILE  any other W with n <= 256 and at most 8 neighbours
+ *     per worker, including rings and tori off the list above.  Same HBM
+ *     bytes, but the rounds run at LDS bandwidth: per phase about
+ *     0.9 ms + K * 0.16 ms at n = 256, d = 1 M (bf16 state), where HBM alone
+ *     would take 0.6 ms: 4 to 5 times the register family's time per byte
+ *     at K = 16, on par with it at K = 1.
+ *   DETAG_KERNEL_PER_ROUND  everything else (n > 256, a worker with more than 8
+ *     neighbours), or DETAG_PATH_PER_ROUND: one launch per round, 12 B per
+ *     element and round (24 + 8*(3K-1) B per element and phase: 208 B at K = 8,
+ *     nine times the on-chip families).
+ *   DETAG_KERNEL_DENSE  only after detag_set_path(DETAG_PATH_DENSE).
+ */
+typedef enum {
+  DETAG_KERNEL_PER_ROUND = 0,
+  DETAG_KERNEL_REGISTER_TILE = 1,
+  DETAG_KERNEL_LDS_TILE = 2,
+  DETAG_KERNEL_DENSE = 3
+} detag_kernel;
+detag_status detag_get_kernel(const detag_ctx *ctx, int32_t *kernel /* detag_kernel */);
 
 /* 1 if the fused (all K rounds on chip) kernels exist for this context, else 0. */
 int32_t detag_has_fused(const detag_ctx *ctx);
@@ -189,7 +223,7 @@ detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double
  *   F, C, B > 0 for detag_grad_softmax_bf16 with those sizes; zeros skip.
  * Both may allocate and block; call them outside any capture.
  */
-detag_status detag_reserve_gossip(detag_ctx *ctx, detag_path path, int32_t K, double eta);
+detag_status detag_reserve_gossip(detag_ctx *ctx, int32_t path /* detag_path */, int32_t K, double eta);
 detag_status detag_reserve_gradient(detag_ctx *ctx, int32_t m, int32_t F, int32_t C, int32_t B);
 
 /*
@@ -219,7 +253,7 @@ detag_status detag_track(detag_ctx *ctx, void *Y_dev, const float *Gnew_dev, con
  */
 detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *Gnew_dev,
                         const float *Gold_dev, double alpha, int32_t K, double eta,
-                        detag_variant variant, void *stream);
+                        int32_t variant /* detag_variant */, void *stream);
 
 /*
  * D-PSGD, the baseline of the "Experiments" section: X <- W^T X - alpha*G,

@@ -16,7 +16,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdetag.so")
+LIB_PATH = os.environ.get("DETAG_LIB") or os.path.join(_HERE, "libdetag.so")
 
 # enums of detag.h
 DETAG_OK, DETAG_EINVAL, DETAG_ENOT_DOUBLY_STOCHASTIC, DETAG_EDISCONNECTED, DETAG_EUNSUPPORTED, DETAG_ENOMEM, DETAG_EHIP = range(7)
@@ -25,12 +25,13 @@ DETAG_TOPO_RING, DETAG_TOPO_TORUS2D, DETAG_TOPO_RANDOM_REGULAR, DETAG_TOPO_EDGES
 DETAG_W_UNIFORM, DETAG_W_METROPOLIS = 0, 1
 DETAG_VARIANT_ATC, DETAG_VARIANT_ALG2 = 0, 1
 DETAG_PATH_AUTO, DETAG_PATH_PER_ROUND, DETAG_PATH_FUSED, DETAG_PATH_DENSE = 0, 1, 2, 3
+DETAG_KERNEL_PER_ROUND, DETAG_KERNEL_REGISTER_TILE, DETAG_KERNEL_LDS_TILE, DETAG_KERNEL_DENSE = 0, 1, 2, 3
 
 _STATUS_NAMES = ["DETAG_OK", "DETAG_EINVAL", "DETAG_ENOT_DOUBLY_STOCHASTIC", "DETAG_EDISCONNECTED",
                  "DETAG_EUNSUPPORTED", "DETAG_ENOMEM", "DETAG_EHIP"]
 
 EXPORTS = ["detag_create", "detag_destroy", "detag_get_spectrum", "detag_get_csr", "detag_set_path",
-           "detag_get_phase_length", "detag_get_gossip_polynomial", "detag_has_fused", "detag_reserve_gossip", "detag_reserve_gradient", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
+           "detag_get_phase_length", "detag_get_gossip_polynomial", "detag_has_fused", "detag_get_kernel", "detag_reserve_gossip", "detag_reserve_gradient", "detag_gossip_accel", "detag_track", "detag_step", "detag_dpsgd_step", "detag_gossip_round", "detag_accumulate", "detag_phase_end",
            "detag_factors_create", "detag_factors_destroy", "detag_factors_count", "detag_factors_get_csr",
            "detag_factors_get_program",
            "detag_factor_apply", "detag_average_consensus", "detag_defacto_update",
@@ -79,6 +80,8 @@ def lib() -> C.CDLL:
     L.detag_get_csr.restype = C.c_int
     L.detag_set_path.argtypes = [vp, C.c_int]
     L.detag_set_path.restype = C.c_int
+    L.detag_get_kernel.argtypes = [vp, C.POINTER(i32)]
+    L.detag_get_kernel.restype = C.c_int
     L.detag_has_fused.argtypes = [vp]
     L.detag_has_fused.restype = i32
     L.detag_reserve_gossip.argtypes = [vp, C.c_int, i32, f64]
@@ -342,6 +345,12 @@ class Context:
     def set_path(self, path: int):
         self._check(lib().detag_set_path(self._h, path))
 
+    def kernel(self) -> int:
+        """detag_get_kernel: the kernel family (DETAG_KERNEL_*) the gossip and phase calls use with the current path."""
+        k = C.c_int32()
+        self._check(lib().detag_get_kernel(self._h, C.byref(k)))
+        return k.value
+
     def has_fused(self) -> bool:
         return bool(lib().detag_has_fused(self._h))
 
@@ -497,6 +506,7 @@ def detag_get_phase_length(ctx: Context, outer_ratio=0.0): return ctx.phase_leng
 def detag_get_gossip_polynomial(ctx: Context, K, eta=-1.0): return ctx.gossip_polynomial(K, eta)
 def detag_set_path(ctx: Context, path: int): ctx.set_path(path)
 def detag_has_fused(ctx: Context): return ctx.has_fused()
+def detag_get_kernel(ctx: Context): return ctx.kernel()
 def detag_reserve_gossip(ctx: Context, path, K=1, eta=-1.0): ctx.reserve_gossip(path, K, eta)
 def detag_reserve_gradient(ctx: Context, m=0, F=0, C_classes=0, B=0): ctx.reserve_gradient(m, F, C_classes, B)
 def detag_gossip_accel(ctx: Context, Z, K, eta=-1.0): ctx.gossip_accel(Z, K, eta)

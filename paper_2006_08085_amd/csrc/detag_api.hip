@@ -264,7 +264,7 @@ detag_status check_f32_ptr(const detag_ctx *ctx, const void *p, const char *name
 
 extern "C" {
 
-detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int64_t ld, detag_dtype state,
+detag_status detag_create(const detag_topology *topo, int32_t n, int64_t d, int64_t ld, int32_t state,
                           detag_ctx **out) {
   if (!out) return set_err(nullptr, DETAG_EINVAL, "out is NULL");
   *out = nullptr;
@@ -379,7 +379,7 @@ detag_status detag_get_csr(const detag_ctx *ctx, int32_t *n, int64_t *nnz, const
   return DETAG_OK;
 }
 
-detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
+detag_status detag_set_path(detag_ctx *ctx, int32_t path) {
   if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
   if (path != DETAG_PATH_AUTO && path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_FUSED && path != DETAG_PATH_DENSE)
     return set_err(ctx, DETAG_EINVAL, "unknown path");
@@ -387,7 +387,19 @@ detag_status detag_set_path(detag_ctx *ctx, detag_path path) {
     return set_err(ctx, DETAG_EUNSUPPORTED, "the dense path needs n <= 256");
   if (path == DETAG_PATH_FUSED && !detag_has_fused(ctx))
     return set_err(ctx, DETAG_EUNSUPPORTED, "no fused kernel for this topology and n");
-  ctx->path = path;
+  ctx->path = static_cast<detag_path>(path);
+  return DETAG_OK;
+}
+
+detag_status detag_get_kernel(const detag_ctx *ctx, int32_t *kernel) {
+  if (!ctx) return set_err(nullptr, DETAG_EINVAL, "ctx is NULL");
+  if (!kernel) return set_err(ctx, DETAG_EINVAL, "kernel is NULL");
+  Chosen c;
+  if (detag_status st = choose_path(ctx, &c)) return st;
+  *kernel = c == kFusedStructured ? DETAG_KERNEL_REGISTER_TILE
+          : c == kFusedGeneric    ? DETAG_KERNEL_LDS_TILE
+          : c == kDense           ? DETAG_KERNEL_DENSE
+                                  : DETAG_KERNEL_PER_ROUND;
   return DETAG_OK;
 }
 
@@ -412,7 +424,7 @@ detag_status detag_get_gossip_polynomial(const detag_ctx *ctx, int32_t K, double
   return DETAG_OK;
 }
 
-detag_status detag_reserve_gossip(detag_ctx *ctx, detag_path path, int32_t K, double eta) {
+detag_status detag_reserve_gossip(detag_ctx *ctx, int32_t path, int32_t K, double eta) {
   if (detag_status st = need_device(ctx)) return st;
   if (path != DETAG_PATH_PER_ROUND && path != DETAG_PATH_DENSE)
     return set_err(ctx, DETAG_EINVAL, "only DETAG_PATH_PER_ROUND and DETAG_PATH_DENSE own memory to reserve");
@@ -478,7 +490,7 @@ detag_status detag_track(detag_ctx *ctx, void *Y_dev, const float *Gnew_dev, con
 }
 
 detag_status detag_step(detag_ctx *ctx, void *X_dev, void *Y_dev, const float *Gnew_dev, const float *Gold_dev,
-                        double alpha, int32_t K, double eta, detag_variant variant, void *stream) {
+                        double alpha, int32_t K, double eta, int32_t variant, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
   if (detag_status st = check_state_ptr(ctx, Y_dev, "Y_dev")) return st;

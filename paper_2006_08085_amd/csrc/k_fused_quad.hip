@@ -64,7 +64,22 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadr
     lb[i] = buf_load<float>(row_of(b, tile, ld, i, valid), fo);
   }
   __builtin_amdgcn_sched_barrier(0);
-  float z[4] = {0.f, 0.f, 0.f, 0.f};
+  // All the noise of the tile is generated now, while the first rows' loads are in flight, and parked in p
+  // (free until the rounds).  Generated inside the row loop instead, the Philox and Box-Muller arithmetic
+  // spaces the loads out: fewer reads in flight, 2 % more kernel time on the 8x8 torus at d = 11.2 M.
+  if (sigma != 0.f) {
+#pragma unroll
+    for (int i = 0; i < N; i += 4) {  // noise of rows i..i+3 at this lane's column
+      float z[4];
+      normal4(q, uint32_t(i) + j, step, seed_lo, seed_hi, z);
+      quad_transpose(z, j);
+      p[i] = z[0], p[i + 1] = z[1], p[i + 2] = z[2], p[i + 3] = z[3];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) p[i] = 0.f;
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     if (i + D < N) {
@@ -73,11 +88,7 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadr
       lg[i + D] = buf_load<float>(row_of(G, tile, ld, i + D, valid), fo);
       lb[i + D] = buf_load<float>(row_of(b, tile, ld, i + D, valid), fo);
     }
-    if ((i & 3) == 0 && sigma != 0.f) {  // noise of rows i..i+3 at this lane's column
-      normal4(q, uint32_t(i) + j, step, seed_lo, seed_hi, z);
-      quad_transpose(z, j);
-    }
-    const float g = fmaf(sigma, z[i & 3], hc * (lx[i] - lb[i]));
+    const float g = fmaf(sigma, p[i], hc * (lx[i] - lb[i]));
     u[i] = fmaf(-alpha, ly[i], lx[i]);
     v[i] = ly[i] + g - lg[i];
     pin_vgpr(v[i]);

@@ -346,3 +346,103 @@ def test_device_calls_fail_loudly_without_a_gpu():
     st = D.lib().detag_gossip_accel(ctx._h, C.c_void_p(4096), 2, -1.0, None)
     assert st == D.DETAG_EHIP
     assert b"GPU" in D.lib().detag_last_error(ctx._h)
+
+
+def test_which_kernel_a_topology_gets():
+    """The kernel family is a function of (topology, n, path); the families differ in cost by integer factors
+    (see detag_get_kernel in detag.h), so the table is pinned."""
+    REG, LDS, PER, DENSE = D.DETAG_KERNEL_REGISTER_TILE, D.DETAG_KERNEL_LDS_TILE, D.DETAG_KERNEL_PER_ROUND, D.DETAG_KERNEL_DENSE
+    ring = {1: LDS, 2: LDS, 3: LDS, 4: REG, 5: LDS, 7: LDS, 8: REG, 12: LDS, 16: REG, 24: LDS, 32: REG, 33: LDS, 64: REG,
+            65: LDS, 128: LDS, 256: LDS, 257: PER}
+    for n, want in ring.items():
+        assert D.detag_create(D.Topology.ring(), n, 16).kernel() == want, ("ring", n)
+    torus = {(4, 4): REG, (4, 8): REG, (8, 8): REG, (8, 4): LDS, (2, 8): LDS, (3, 5): LDS, (16, 16): LDS, (16, 17): PER}
+    for (r, c), want in torus.items():
+        assert D.detag_create(D.Topology.torus(r, c), r * c, 16).kernel() == want, ("torus", r, c)
+    assert D.detag_create(D.Topology.ring(kappa=0.3), 16, 16).kernel() == REG          # the slack matrix keeps the pattern
+    assert D.detag_create(D.Topology.random_regular(4, 0), 256, 16).kernel() == LDS
+    assert D.detag_create(D.Topology.random_regular(4, 0), 300, 16).kernel() == PER
+    star = np.array([(0, j) for j in range(1, 14)])                                     # hub with 13 neighbours
+    assert D.detag_create(D.Topology.from_edges(star), 14, 16).kernel() == PER
+    ring16_as_edges = D.detag_create(D.Topology.from_edges(gen.edges_ring(16), D.DETAG_W_UNIFORM), 16, 16)
+    assert ring16_as_edges.kernel() in (REG, LDS)                                       # the same W given as an edge list
+    ctx = D.detag_create(D.Topology.ring(), 8, 16)
+    ctx.set_path(D.DETAG_PATH_PER_ROUND)
+    assert ctx.kernel() == PER
+    ctx.set_path(D.DETAG_PATH_DENSE)
+    assert ctx.kernel() == DENSE
+    ctx.set_path(D.DETAG_PATH_AUTO)
+    assert ctx.kernel() == REG
+
+
+def test_more_rejections_and_degenerate_sizes():
+    import ctypes as C
+    L = D.lib()
+    h = C.c_void_p()
+    topo = D.Topology.ring()._as_struct()
+    assert L.detag_create(None, 4, 4, 4, D.DETAG_F32, C.byref(h)) == D.DETAG_EINVAL          # NULL topology
+    assert L.detag_create(C.byref(topo), 4, 4, 4, D.DETAG_F32, None) == D.DETAG_EINVAL       # NULL out
+    assert L.detag_last_error(None)
+    csr = D.Topology.from_dense(T.mixing_matrix(4, gen.edges_ring(4)))
+    for field in ("rowptr", "colidx", "vals"):                                               # CSR with a missing array
+        t = D.Topology(D.DETAG_TOPO_CSR, rowptr=csr.rowptr, colidx=csr.colidx, vals=csr.vals)
+        setattr(t, field, None)
+        with pytest.raises(D.DetagError) as ei:
+            D.detag_create(t, 4, 4)
+        assert ei.value.status == D.DETAG_EINVAL
+    bad_ptr = D.Topology(D.DETAG_TOPO_CSR, rowptr=np.array([0, 3, 2, 9, 12], np.int32), colidx=csr.colidx, vals=csr.vals)
+    bad_col = D.Topology(D.DETAG_TOPO_CSR, rowptr=csr.rowptr, colidx=np.where(csr.colidx == 3, 7, csr.colidx).astype(np.int32), vals=csr.vals)
+    nan_val = D.Topology(D.DETAG_TOPO_CSR, rowptr=csr.rowptr, colidx=csr.colidx, vals=np.where(np.arange(len(csr.vals)) == 1, np.nan, csr.vals))
+    for t in (bad_ptr, bad_col, nan_val, D.Topology.ring(kappa=float("nan")), D.Topology.torus(0, 4), D.Topology.torus(-2, -2),
+              D.Topology.random_regular(4, 0, weights=7)):
+        with pytest.raises(D.DetagError) as ei:
+            D.detag_create(t, 4, 4)
+        assert ei.value.status in (D.DETAG_EINVAL, D.DETAG_ENOT_DOUBLY_STOCHASTIC), ei.value
+    with pytest.raises(D.DetagError):
+        D.detag_create(D.Topology.random_regular(4, 0), 4, 4)                                # n <= degree
+    # degenerate sizes are accepted: one worker (W = [1], eta = 0), two workers
+    one = D.detag_create(D.Topology.ring(), 1, 3)
+    assert one.dense_W().tolist() == [[1.0]] and one.spectrum()["eta"] == 0.0 and one.phase_length() == 1
+    two = D.detag_create(D.Topology.ring(), 2, 3)
+    assert np.allclose(two.dense_W(), [[0.5, 0.5], [0.5, 0.5]]) and two.spectrum()["lam"] == pytest.approx(0.0, abs=1e-15)
+    R = C.c_int32()
+    assert L.detag_get_phase_length(two._h, float("nan"), C.byref(R)) == D.DETAG_EINVAL
+    assert L.detag_get_phase_length(two._h, 0.0, None) == D.DETAG_EINVAL
+    P = np.empty((2, 2))
+    assert L.detag_get_gossip_polynomial(two._h, 3, float("nan"), P.ctypes.data_as(C.POINTER(C.c_double))) == D.DETAG_EINVAL
+    assert L.detag_get_gossip_polynomial(two._h, -1, 0.1, P.ctypes.data_as(C.POINTER(C.c_double))) == D.DETAG_EINVAL
+    assert L.detag_get_gossip_polynomial(two._h, 0, 0.1, P.ctypes.data_as(C.POINTER(C.c_double))) == D.DETAG_OK and np.array_equal(P, np.eye(2))
+    k = C.c_int32()
+    assert L.detag_get_kernel(None, C.byref(k)) == D.DETAG_EINVAL and L.detag_get_kernel(two._h, None) == D.DETAG_EINVAL
+    with pytest.raises(D.DetagError):
+        D.Factors(two, root=5)                                                               # root outside the graph
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_graphs_build_and_agree_with_the_oracle(seed):
+    """Random connected graphs of random size and degree, Metropolis weights: the library's W, spectrum and the
+    factor sequence of the exact average against the oracle's."""
+    from oracle import consensus as OC
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(2, 40))
+    e = {(i, i + 1) for i in range(n - 1)}
+    for _ in range(int(rng.integers(0, 3 * n))):
+        a, b = sorted(rng.integers(0, n, 2).tolist())
+        if a != b:
+            e.add((a, b))
+    e = np.array(sorted(e), dtype=np.int64).reshape(-1, 2)
+    if len(e) == 0:
+        pytest.skip("no edge")
+    ctx = D.detag_create(D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), n, 8)
+    W = T.mixing_matrix(n, e, "metropolis")
+    assert np.allclose(ctx.dense_W(), W, rtol=0, atol=1e-15)
+    assert ctx.spectrum()["lam"] == pytest.approx(T.spectrum(W)[2], abs=1e-11)
+    root = int(rng.integers(0, n))
+    f = D.Factors(ctx, root)
+    ref = OC.gather_propagate_factors(n, e, root)
+    assert f.R == len(ref)
+    prod = np.eye(n)
+    for r in range(f.R):
+        assert np.allclose(f.dense(r), ref[r], rtol=0, atol=1e-15)
+        prod = f.dense(r) @ prod
+    assert np.allclose(prod, np.full((n, n), 1.0 / n), atol=1e-12)
