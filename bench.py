@@ -30,6 +30,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+LDS_PEAK_GBS = 256 * 128 * 2.4  # 256 compute units x 128 B per clock x 2.4 GHz = 78,643 GB/s
 PHASE_BYTES_PER_ELEMENT = 24   # detag_step, fp32: read X, Y, G_new, G_old; write X, Y (independent of K)
 FUSED_BYTES_PER_ELEMENT = 28   # detag_step_quadratic, fp32: read X, Y, G, b; write X, Y, G
 DPSGD_BYTES_PER_ELEMENT = 12   # detag_dpsgd_step, fp32: read X, G; write X
@@ -318,6 +319,18 @@ def main():
                      "algorithmic_bytes_per_launch": bpe * E,
                      **({"note": note} if note else {})},
     }
+    if what == "step" and alg == "detag" and not structured and not args.dense and not per_round:
+        # the K rounds of the kernel for arbitrary W run out of LDS: per output and round it reads the neighbours'
+        # values (table width: the degree rounded up to 2, 4 or 8) and writes its own, 4 bytes each, for X and for Y
+        width = 2 if cfg.degree <= 2 else 4 if cfg.degree <= 4 else 8
+        lds_bytes = (width + 1) * 4 * E * K * 2
+        lds_rate = lds_bytes / (phase_ms * 1e-3) / 1e9
+        out["roofline"].update({"bound": "lds", "achieved": lds_rate, "peak": LDS_PEAK_GBS, "frac": lds_rate / LDS_PEAK_GBS,
+                                "lds_bytes_per_launch": lds_bytes, "hbm_achieved": achieved, "hbm_peak": HBM_PEAK_GBS,
+                                "hbm_frac": achieved / HBM_PEAK_GBS,
+                                "note": "the rounds run out of LDS: achieved/peak are LDS bytes over the whole kernel "
+                                        "against 256 CUs x 128 B/clk x 2.4 GHz; hbm_* give the HBM side of the same launch"})
+        out["roofline"].pop("bar", None)
     if what == "diag":
         ce_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
         out["roofline"]["consensus_error_ms"] = ce_ms      # two kernels; the second pass over a column comes from cache

@@ -11,7 +11,8 @@
 // in place: row i of the old gradient is read just before the new one is stored.
 //
 // Same register-resident layout as the plain fused phase (one lane = one
-// column, all n rows in VGPRs).  The Gaussian noise is counter-based; one
+// column, all n rows on chip; for 64 workers part of the tracker side waits in
+// LDS, see kParkedRows).  The Gaussian noise is counter-based; one
 // Philox block yields the four normals of four adjacent columns of one worker,
 // so the four lanes of a quad each generate the block of one of four
 // consecutive rows and exchange the results with two DPP quad permutes (a 4x4
@@ -41,20 +42,29 @@ __device__ __forceinline__ void quad_transpose(float (&a)[4], unsigned j) {
   a[0] = hi ? s0 : c0, a[1] = hi ? s1 : c1, a[2] = hi ? c2 : s0, a[3] = hi ? c3 : s1;
 }
 
+// Rows of the tracker side parked in LDS while the model side runs its rounds, for patterns of 64 workers.
+// With all three arrays (u, v and the round scratch p) in registers a lane needs 192 + staging registers, two
+// wavefronts per SIMD; with 48 of v's 64 rows in LDS (48 KiB per block, each lane reading back only what it
+// wrote: no barrier) it needs 146, three wavefronts per SIMD and three blocks per compute unit, which hides
+// more of the noise and round arithmetic under the other blocks' memory phases.
+constexpr int kParkedRows = 48;
 template <class T, typename ST>
-__global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadratic_kernel(
+__global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1))) void fused_quadratic_kernel(
     ST *X, ST *Y, float *G, const float *__restrict__ h, const float *__restrict__ b, int64_t d, int64_t ld, Coef c,
     float alpha, int K, float sigma, uint32_t seed_lo, uint32_t seed_hi, uint32_t step) {
   constexpr int N = T::n;
   static_assert(N % 4 == 0, "rows are processed in groups of four");
+  constexpr int NL = N >= 64 ? kParkedRows : 0;
+  constexpr int NR = N - NL;
   constexpr int D = kRowsAhead < N ? kRowsAhead : N;
+  __shared__ float vl[NL > 0 ? NL * kThreads : 1];
   const int64_t tile = xcd_tile(blockIdx.x, gridDim.x) * kThreads;
   const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
   const uint32_t so = threadIdx.x * uint32_t(sizeof(ST)), fo = threadIdx.x * 4u;
   const unsigned j = threadIdx.x & 3u;
   const uint64_t q = uint64_t(tile + threadIdx.x) >> 2;
   const float hc = buf_load<float>(make_rsrc(h + tile, valid * 4u), fo);
-  float u[N], v[N], p[N];
+  float u[N], p[N], vr[NR > 0 ? NR : 1];
   float lx[N], ly[N], lg[N], lb[N];
 #pragma unroll
   for (int i = 0; i < D; ++i) {
@@ -90,8 +100,10 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadr
     }
     const float g = fmaf(sigma, p[i], hc * (lx[i] - lb[i]));
     u[i] = fmaf(-alpha, ly[i], lx[i]);
-    v[i] = ly[i] + g - lg[i];
-    pin_vgpr(v[i]);
+    float vi = ly[i] + g - lg[i];
+    pin_vgpr(vi);
+    if (i < NR) vr[i] = vi;
+    else vl[(i - NR) * kThreads + threadIdx.x] = vi;
     buf_store<float>(row_of(G, tile, ld, i, valid), fo, g);
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -99,13 +111,17 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 1)) void fused_quadr
   __builtin_amdgcn_sched_barrier(0);
   X = launder_uniform(X);
 #pragma unroll
-  for (int i = 0; i < N; ++i) buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+  for (int i = 0; i < N; ++i) {
+    buf_store<ST>(row_of(X, tile, ld, i, valid), so, u[i]);
+    if (i < NR) u[i] = vr[i];
+    else u[i] = vl[(i - NR) * kThreads + threadIdx.x];
+  }
   __builtin_amdgcn_sched_barrier(0);
-  ag_rounds<T>(v, p, c, K);
+  ag_rounds<T>(u, p, c, K);
   __builtin_amdgcn_sched_barrier(0);
   Y = launder_uniform(Y);
 #pragma unroll
-  for (int i = 0; i < N; ++i) buf_store<ST>(row_of(Y, tile, ld, i, valid), so, v[i]);
+  for (int i = 0; i < N; ++i) buf_store<ST>(row_of(Y, tile, ld, i, valid), so, u[i]);
 }
 
 template <class T>
