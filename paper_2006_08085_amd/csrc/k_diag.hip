@@ -13,6 +13,12 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// X is read once per kernel: non-temporal.
+__device__ __forceinline__ float stream_f32(const float *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float stream_f32(const bf16_t *p) {
+  return __uint_as_float(uint32_t(__builtin_nontemporal_load(&p->bits)) << 16);
+}
+
 template <typename ST>
 __global__ __launch_bounds__(kThreads) void mean_kernel(int n, int64_t d, int64_t ld, const ST *__restrict__ X,
                                                         float *__restrict__ xbar) {
@@ -20,7 +26,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(int n, int64_t d, int64_
   if (c >= d) return;
   double s = 0.0;
 #pragma unroll 16
-  for (int i = 0; i < n; ++i) s += double(to_f32(X[int64_t(i) * ld + c]));  // 16 rows' loads in flight
+  for (int i = 0; i < n; ++i) s += double(stream_f32(X + int64_t(i) * ld + c));  // 16 rows' loads in flight
   xbar[c] = float(s / n);
 }
 
@@ -47,11 +53,11 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(int n, int6
     //   sum_i (x_i - mean)^2 = sum_i e_i^2 - (sum_i e_i)^2 / n.
     // Both terms are of the size of the result (the shift by x_0 removes the common part of the column), so the
     // subtraction does not cancel, however close the workers are to agreement.
-    const double x0 = double(to_f32(X[c]));
+    const double x0 = double(stream_f32(X + c));
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll 16
     for (int i = 1; i < n; ++i) {
-      const double e = double(to_f32(X[int64_t(i) * ld + c])) - x0;
+      const double e = double(stream_f32(X + int64_t(i) * ld + c)) - x0;
       s1 += e;
       s2 = fma(e, e, s2);
     }

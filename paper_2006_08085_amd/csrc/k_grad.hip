@@ -14,6 +14,8 @@ namespace detag {
 namespace {
 
 constexpr int kThreads = 256;
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
 
 template <typename ST, bool VEC>
 __global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int64_t ld, const ST *__restrict__ X,
@@ -30,20 +32,21 @@ __global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int
   const int64_t off = int64_t(i) * ld + c0;
   float x[4], hv[4], bv[4], z[4] = {0.f, 0.f, 0.f, 0.f};
   if (VEC && valid == 4) {
+    // X, b, the noise array and G are touched once: non-temporal; h is read again for every worker row: cached
     if constexpr (sizeof(ST) == 4) {
-      const float4 t = *reinterpret_cast<const float4 *>(X + off);
+      const vf4_t t = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(X + off));
       x[0] = t.x, x[1] = t.y, x[2] = t.z, x[3] = t.w;
     } else {
-      const uint2 t = *reinterpret_cast<const uint2 *>(X + off);
+      const vu2_t t = __builtin_nontemporal_load(reinterpret_cast<const vu2_t *>(X + off));
       x[0] = __uint_as_float(t.x << 16), x[1] = __uint_as_float(t.x & 0xffff0000u);
       x[2] = __uint_as_float(t.y << 16), x[3] = __uint_as_float(t.y & 0xffff0000u);
     }
     const float4 th = *reinterpret_cast<const float4 *>(h + int64_t(i) * h_row_stride + c0);
-    const float4 tb = *reinterpret_cast<const float4 *>(b + off);
+    const vf4_t tb = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(b + off));
     hv[0] = th.x, hv[1] = th.y, hv[2] = th.z, hv[3] = th.w;
     bv[0] = tb.x, bv[1] = tb.y, bv[2] = tb.z, bv[3] = tb.w;
     if (noise) {
-      const float4 tz = *reinterpret_cast<const float4 *>(noise + off);
+      const vf4_t tz = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(noise + off));
       z[0] = tz.x, z[1] = tz.y, z[2] = tz.z, z[3] = tz.w;
     }
   } else {
@@ -63,7 +66,8 @@ __global__ __launch_bounds__(kThreads) void grad_quadratic_kernel(int64_t d, int
 #pragma unroll
   for (int e = 0; e < 4; ++e) g[e] = fmaf(sigma, z[e], hv[e] * (x[e] - bv[e]));
   if (VEC && valid == 4) {
-    *reinterpret_cast<float4 *>(G + off) = make_float4(g[0], g[1], g[2], g[3]);
+    const vf4_t tg = {g[0], g[1], g[2], g[3]};
+    __builtin_nontemporal_store(tg, reinterpret_cast<vf4_t *>(G + off));
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
