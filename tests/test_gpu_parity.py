@@ -440,7 +440,7 @@ def test_config5_shape_bf16_short_run():
 # ---------------------------------------------------------------------------
 # gradient query + phase in one kernel
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 16), ("torus48", 32), ("torus88", 64)])
+@pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 16), ("torus48", 32), ("torus88", 64), ("ring", 64)])
 @pytest.mark.parametrize("sigma", [0.0, 0.1])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma, dtype):
