@@ -248,7 +248,7 @@ def main():
     # K-round kernels; one launch per round moves every round through HBM (fp32 scratch whatever the state type)
     if what == "gossip":
         bpe = rounds_bytes if per_round else 2 * sb
-        kernel = ("gossip_round_kernel x%d" % K) if per_round else \
+        kernel = ("gossip_round_tile_kernel x%d" % K) if per_round and n <= 256 else ("gossip_round_kernel x%d" % K) if per_round else \
             ("fused_structured_kernel, gossip mode" if structured else "fused_generic_kernel, gossip mode")
         kernel += " (detag_gossip_accel)"
     elif what == "stream":
@@ -266,7 +266,8 @@ def main():
         kernel = "fused_quadratic_kernel (detag_step_quadratic)"
     elif per_round:
         bpe = 24 + 2 * rounds_bytes
-        kernel = "elementwise_kernel + gossip_round_kernel x%d (detag_step, one launch per round)" % (2 * K)
+        kernel = "elementwise_kernel + %s x%d (detag_step, one launch per round)" % (
+            "gossip_round_tile_kernel" if n <= 256 else "gossip_round_kernel", 2 * K)
         note = "sum over the launches of one detag_step call; every round crosses HBM"
     else:
         bpe = 4 * sb + 8

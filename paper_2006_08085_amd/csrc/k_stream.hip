@@ -123,17 +123,23 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(int n, int64_t d
   }
 }
 
-// The same round with the neighbour tile staged in LDS, for n <= kTileRowsMax workers.  A block of four
-// wavefronts owns 64 columns and all n rows of them: row i of z_r is loaded once (wavefront i mod 4, 256
-// contiguous bytes), parked in LDS as fp32, and after one barrier every output row takes its neighbours from
+// The same round with the neighbour tile staged in LDS, for n <= kTileRowsMax workers.  A block of kTileWaves
+// wavefronts owns 64 columns and all n rows of them: row i of z_r is loaded once (wavefront i mod kTileWaves,
+// 256 contiguous bytes), parked in LDS as fp32, and after one barrier every output row takes its neighbours from
 // there.  HBM sees z_r once, z_{r-1} (or G) once and the output once: 12 bytes per element, where the kernel
 // above re-fetches every row once per neighbour that reads it.  Row indices are uniform in a wavefront, so the
 // CSR row (pointers, columns, weights) is read with scalar loads.  Every access goes through a buffer resource:
-// the ragged last tile and odd pitches need no separate path.
-constexpr int kTileCols = 64, kTileWaves = 4, kTileThreads = 64 * kTileWaves, kTileRowsMax = 256, kTileBatch = 4;
+// the ragged last tile and odd pitches need no separate path.  The launcher takes this kernel for matrices of
+// kTileMinBytes and more, with 4, 8 or 16 wavefronts per block for n <= 64, 128, 256 (about 16 rows per wavefront;
+// fewer wavefronts keep too few loads in flight at large n).  Measured per round, fp32: 8x8 torus at 256 MiB
+// 188 us against 236 us for the kernel above, at 1 GiB 696 against 960 us; random 4-regular graph, n = 256, 1 GiB:
+// 750 against 1210 us.  Below about 128 MiB the caches serve the re-reads of the kernel above and it is the
+// faster one (64 MiB: 46 against 53 us), so it keeps those.
+constexpr int kTileCols = 64, kTileRowsMax = 256, kTileBatch = 4;
+constexpr int64_t kTileMinBytes = int64_t(128) << 20;
 
-template <typename ST, bool HAS_G>
-__global__ __launch_bounds__(kTileThreads) void gossip_round_tile_kernel(int n, int64_t d, int64_t ld,
+template <typename ST, bool HAS_G, int kTileWaves>
+__global__ __launch_bounds__(64 * kTileWaves) void gossip_round_tile_kernel(int n, int64_t d, int64_t ld,
                                                                          const int32_t *__restrict__ rowptr,
                                                                          const int32_t *__restrict__ colidx,
                                                                          const float *__restrict__ vals,
@@ -338,13 +344,17 @@ template <typename ST, bool HAS_G>
 int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, const float *G,
                    float c_mix, float eta, float alpha, void *stream) {
   auto st = static_cast<hipStream_t>(stream);
-  // narrow matrices (fewer column tiles than compute units) keep the form below, which also splits the rows over blocks
-  if (s.n <= kTileRowsMax && s.d >= int64_t(kTileCols) * 256) {
+  if (s.n <= kTileRowsMax && int64_t(s.n) * s.ld * int64_t(sizeof(ST)) >= kTileMinBytes) {
     const dim3 tgrid(ceil_div_i64(s.d, kTileCols));
     const size_t lds_bytes = size_t(s.n) * kTileCols * sizeof(float);
-    gossip_round_tile_kernel<ST, HAS_G><<<tgrid, kTileThreads, lds_bytes, st>>>(
-        s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev),
-        static_cast<ST *>(out), G, c_mix, eta, alpha);
+#define DETAG_TILE_GO(RW)                                                                                      \
+  gossip_round_tile_kernel<ST, HAS_G, RW><<<tgrid, 64 * RW, lds_bytes, st>>>(                                  \
+      s.n, s.d, s.ld, w.rowptr, w.colidx, w.vals, static_cast<const ST *>(cur), static_cast<const ST *>(prev), \
+      static_cast<ST *>(out), G, c_mix, eta, alpha)
+    if (s.n <= 64) DETAG_TILE_GO(4);
+    else if (s.n <= 128) DETAG_TILE_GO(8);
+    else DETAG_TILE_GO(16);
+#undef DETAG_TILE_GO
     return hip_rc(hipGetLastError());
   }
   const bool vec = vec_ok(s, {cur, prev, out}, {G});
