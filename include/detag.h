@@ -399,14 +399,18 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
  *   G+ = h*(X - b) + sigma*z;  X+ = M(X - alpha*Y);  Y+ = M(Y + G+ - G).
  * G_dev (fp32 n x ld) holds the previous gradient buffer g(k-1) on entry and
  * g(k) on return, so the caller keeps ONE gradient matrix and does not swap.
- * h_dev: fp32, length ld, shared by all workers; b_dev: fp32 n x ld; noise is
+ * h_dev: fp32, length ld and shared by all workers (h_per_worker = 0), or
+ * n x ld with one row per worker (h_per_worker != 0, one more streamed array);
+ * b_dev: fp32 n x ld; noise is
  * always the counter-based generator of detag_grad_quadratic_diag (sigma = 0
  * turns it off).  Results are identical to the two separate calls.
  * Only for contexts on a ring or 2-D torus with a register-resident kernel and
- * K >= 1 (DETAG_EUNSUPPORTED otherwise).  X, Y, G, b must not overlap.
+ * K >= 1 (DETAG_EUNSUPPORTED otherwise).  X, Y, G, h, b must not overlap.
+ * Algorithm 2 as printed (DETAG_VARIANT_ALG2) has no one-kernel form: use the
+ * two separate calls.
  */
 detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
-                                  const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
+                                  int32_t h_per_worker, const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
                                   int32_t K, double eta, void *stream);
 
 /*

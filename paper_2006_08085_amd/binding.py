@@ -127,7 +127,7 @@ def lib() -> C.CDLL:
     L.detag_consensus_error_static.restype = C.c_int
     L.detag_grad_quadratic_diag.argtypes = [vp, vp, vp, i32, vp, vp, f32, u64, u32, vp, vp]
     L.detag_grad_quadratic_diag.restype = C.c_int
-    L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, vp, f32, u64, u32, f64, i32, f64, vp]
+    L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, i32, vp, f32, u64, u32, f64, i32, f64, vp]
     L.detag_step_quadratic.restype = C.c_int
     L.detag_grad_lstsq.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     L.detag_grad_lstsq.restype = C.c_int
@@ -446,11 +446,17 @@ class Context:
 
     def step_quadratic(self, X, Y, G, h, b, alpha: float, K: int, sigma: float = 0.0, seed: int = 0, step: int = 0,
                        eta: float = -1.0):
+        """h: a float32 vector of length >= d shared by the workers, or an n x ld matrix with one row per worker."""
         import torch
-        if h.dtype != torch.float32 or not h.is_cuda or h.dim() != 1 or h.numel() < self.d or not h.is_contiguous():
-            raise ValueError("h must be a contiguous float32 GPU vector of length >= d")
+        per_worker = 1 if h.dim() == 2 else 0
+        if per_worker:
+            hp = self._mat(h, torch.float32, "h")
+        else:
+            if h.dtype != torch.float32 or not h.is_cuda or h.dim() != 1 or h.numel() < self.d or not h.is_contiguous():
+                raise ValueError("h must be a contiguous float32 GPU vector of length >= d")
+            hp = C.c_void_p(h.data_ptr())
         self._check(lib().detag_step_quadratic(self._h, self._state(X, "X"), self._state(Y, "Y"),
-                                               self._mat(G, torch.float32, "G"), C.c_void_p(h.data_ptr()),
+                                               self._mat(G, torch.float32, "G"), hp, per_worker,
                                                self._mat(b, torch.float32, "b"), sigma, seed, step, alpha, K, eta,
                                                self._stream()))
 

@@ -799,7 +799,7 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
 }
 
 detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
-                                  const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
+                                  int32_t h_per_worker, const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
                                   int32_t K, double eta, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
@@ -809,15 +809,16 @@ detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, floa
   if (detag_status st = check_f32_ptr(ctx, b_dev, "b_dev")) return st;
   if (X_dev == Y_dev || static_cast<void *>(G_dev) == X_dev || static_cast<void *>(G_dev) == Y_dev ||
       static_cast<const void *>(b_dev) == X_dev || static_cast<const void *>(b_dev) == Y_dev ||
-      static_cast<const void *>(b_dev) == G_dev)
-    return set_err(ctx, DETAG_EINVAL, "X, Y, G and b must not overlap");
+      static_cast<const void *>(b_dev) == G_dev || static_cast<const void *>(h_dev) == X_dev ||
+      static_cast<const void *>(h_dev) == Y_dev || static_cast<const void *>(h_dev) == G_dev)
+    return set_err(ctx, DETAG_EINVAL, "X, Y, G, h and b must not overlap");
   if (!std::isfinite(alpha) || !std::isfinite(sigma)) return set_err(ctx, DETAG_EINVAL, "alpha and sigma must be finite");
   float e;
   if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
   if (K < 1 || !fused_structured_available(ctx->W) || ctx->path == DETAG_PATH_PER_ROUND)
     return set_err(ctx, DETAG_EUNSUPPORTED,
                    "detag_step_quadratic needs K >= 1 and a ring/torus context with a register-resident kernel");
-  const int rc = launch_fused_quadratic(ctx->shape, ctx->W, X_dev, Y_dev, G_dev, h_dev, b_dev, float(alpha), K, e,
+  const int rc = launch_fused_quadratic(ctx->shape, ctx->W, X_dev, Y_dev, G_dev, h_dev, h_per_worker != 0, b_dev, float(alpha), K, e,
                                         sigma, seed, step, stream);
   return rc ? hip_fail(ctx, "fused gradient + phase", rc) : DETAG_OK;
 }

@@ -48,7 +48,9 @@ __device__ __forceinline__ void quad_transpose(float (&a)[4], unsigned j) {
 // wrote: no barrier) it needs 146, three wavefronts per SIMD and three blocks per compute unit, which hides
 // more of the noise and round arithmetic under the other blocks' memory phases.
 constexpr int kParkedRows = 48;
-template <class T, typename ST>
+// HPW: the curvature h is an n x ld matrix (one row per worker, one more streamed array: 32 B per element) instead
+// of one d-vector shared by all workers.
+template <class T, typename ST, bool HPW>
 __global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1))) void fused_quadratic_kernel(
     ST *X, ST *Y, float *G, const float *__restrict__ h, const float *__restrict__ b, int64_t d, int64_t ld, Coef c,
     float alpha, int K, float sigma, uint32_t seed_lo, uint32_t seed_hi, uint32_t step) {
@@ -63,15 +65,16 @@ __global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1)
   const uint32_t so = threadIdx.x * uint32_t(sizeof(ST)), fo = threadIdx.x * 4u;
   const unsigned j = threadIdx.x & 3u;
   const uint64_t q = uint64_t(tile + threadIdx.x) >> 2;
-  const float hc = buf_load<float>(make_rsrc(h + tile, valid * 4u), fo);
+  const float hc = HPW ? 0.f : buf_load<float>(make_rsrc(h + tile, valid * 4u), fo);
   float u[N], p[N], vr[NR > 0 ? NR : 1];
-  float lx[N], ly[N], lg[N], lb[N];
+  float lx[N], ly[N], lg[N], lb[N], lh[HPW ? N : 1];
 #pragma unroll
   for (int i = 0; i < D; ++i) {
     lx[i] = buf_load<ST>(row_of(X, tile, ld, i, valid), so);
     ly[i] = buf_load<ST>(row_of(Y, tile, ld, i, valid), so);
     lg[i] = buf_load<float>(row_of(G, tile, ld, i, valid), fo);
     lb[i] = buf_load<float>(row_of(b, tile, ld, i, valid), fo);
+    if constexpr (HPW) lh[i] = buf_load<float>(row_of(h, tile, ld, i, valid), fo);
   }
   __builtin_amdgcn_sched_barrier(0);
   // All the noise of the tile is generated now, while the first rows' loads are in flight, and parked in p
@@ -97,8 +100,9 @@ __global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1)
       ly[i + D] = buf_load<ST>(row_of(Y, tile, ld, i + D, valid), so);
       lg[i + D] = buf_load<float>(row_of(G, tile, ld, i + D, valid), fo);
       lb[i + D] = buf_load<float>(row_of(b, tile, ld, i + D, valid), fo);
+      if constexpr (HPW) lh[i + D] = buf_load<float>(row_of(h, tile, ld, i + D, valid), fo);
     }
-    const float g = fmaf(sigma, p[i], hc * (lx[i] - lb[i]));
+    const float g = fmaf(sigma, p[i], (HPW ? lh[i] : hc) * (lx[i] - lb[i]));
     u[i] = fmaf(-alpha, ly[i], lx[i]);
     float vi = ly[i] + g - lg[i];
     pin_vgpr(vi);
@@ -125,27 +129,30 @@ __global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1)
 }
 
 template <class T>
-int launch_s(const Shape &s, void *X, void *Y, float *G, const float *h, const float *b, const Coef &c, float alpha,
-             int K, float sigma, uint64_t seed, uint32_t step, void *stream) {
+int launch_s(const Shape &s, void *X, void *Y, float *G, const float *h, bool hpw, const float *b, const Coef &c,
+             float alpha, int K, float sigma, uint64_t seed, uint32_t step, void *stream) {
   const dim3 grid(ceil_div_i64(s.d, kThreads));
   auto st = static_cast<hipStream_t>(stream);
   const uint32_t slo = uint32_t(seed & 0xffffffffu), shi = uint32_t(seed >> 32);
-  if (s.bf16)
-    fused_quadratic_kernel<T, bf16_t><<<grid, kThreads, 0, st>>>(static_cast<bf16_t *>(X), static_cast<bf16_t *>(Y), G,
-                                                                 h, b, s.d, s.ld, c, alpha, K, sigma, slo, shi, step);
-  else
-    fused_quadratic_kernel<T, float><<<grid, kThreads, 0, st>>>(static_cast<float *>(X), static_cast<float *>(Y), G, h,
-                                                                b, s.d, s.ld, c, alpha, K, sigma, slo, shi, step);
+#define DETAG_QUAD(ST, HPW)                                                                                          \
+  fused_quadratic_kernel<T, ST, HPW><<<grid, kThreads, 0, st>>>(static_cast<ST *>(X), static_cast<ST *>(Y), G, h, b, \
+                                                                s.d, s.ld, c, alpha, K, sigma, slo, shi, step)
+  if (s.bf16) {
+    if (hpw) DETAG_QUAD(bf16_t, true); else DETAG_QUAD(bf16_t, false);
+  } else {
+    if (hpw) DETAG_QUAD(float, true); else DETAG_QUAD(float, false);
+  }
+#undef DETAG_QUAD
   return hip_rc(hipGetLastError());
 }
 
 }  // namespace
 
-int launch_fused_quadratic(const Shape &s, const HostW &W, void *X, void *Y, float *G, const float *h, const float *b,
-                           float alpha, int K, float eta, float sigma, uint64_t seed, uint32_t step, void *stream) {
+int launch_fused_quadratic(const Shape &s, const HostW &W, void *X, void *Y, float *G, const float *h, bool h_per_worker,
+                           const float *b, float alpha, int K, float eta, float sigma, uint64_t seed, uint32_t step, void *stream) {
   if (K < 1 || !fused_structured_available(W)) return -1;
   const Coef c = make_coef(W, eta);
-#define DETAG_GO(T) return launch_s<T>(s, X, Y, G, h, b, c, alpha, K, sigma, seed, step, stream)
+#define DETAG_GO(T) return launch_s<T>(s, X, Y, G, h, h_per_worker, b, c, alpha, K, sigma, seed, step, stream)
   if (W.structure == kRing) {
     switch (W.n) {
       case 4: DETAG_GO(Ring<4>);

@@ -545,3 +545,34 @@ def test_one_round_with_lds_staged_tile(n, graph, dtype, pad):
     zd = to_dev(cur, ld, tdt)
     ctx.gossip_accel(zd, K, eta)
     assert rel_err(to_host(zd, d), OG.accelerated_gossip(cur, W, K, eta), amax(cur)) < tol and padding_ok(zd, d)
+
+
+@pytest.mark.parametrize("kind,n", [("ring", 16), ("torus88", 64)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_step_quadratic_with_per_worker_curvature(kind, n, dtype):
+    """h as an n x ld matrix (every worker its own curvature): against the oracle and bit for bit against
+    detag_grad_quadratic_diag + detag_step on the same inputs."""
+    d, ld, K, alpha, sigma, seed = 700, 704, 4, 0.4, 0.1, 7
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    ctx, W = make_ctx(kind, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    eta = eta_for(W)
+    _, b = gen.quadratic_problem(n, d, seed=3)
+    h = np.exp(np.random.default_rng(5).uniform(np.log(1e-3), 0.0, size=(n, d))).astype(np.float32)
+    X, Y, Go = gen.state(n, d, 1), gen.state(n, d, 2), gen.state(n, d, 3)
+    if bf:
+        X, Y = OO.round_bf16(X), OO.round_bf16(Y)
+    hd, bd = to_dev(h, ld), to_dev(b, ld)
+    Xf, Yf, Gf = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld)
+    Xs, Ys, Gos, Gns = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld), to_dev(np.zeros((n, d)), ld)
+    ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=2)
+    ctx.grad_quadratic_diag(Xs, hd, bd, Gns, sigma=sigma, seed=seed, step=2)
+    ctx.step(Xs, Ys, Gns, Gos, alpha, K)
+    Gn = OO.grad_quadratic_diag(X, h, b, ON.normal_noise(seed, 2, n, np.arange(d)), sigma)
+    Xn, Yn = OG.detag_step(X, Y, Gn, Go, W, alpha, K, eta)
+    S = amax(X, Y, Gn, Go)
+    assert rel_err(to_host(Gf, d), Gn, S) < TOL_F32
+    assert rel_err(to_host(Xf, d), Xn, S) < tol and rel_err(to_host(Yf, d), Yn, S) < tol
+    torch.cuda.synchronize()
+    assert torch.equal(Xf, Xs) and torch.equal(Yf, Ys) and torch.equal(Gf, Gns)
+    assert padding_ok(Xf, d) and padding_ok(Yf, d) and padding_ok(Gf, d) and padding_ok(hd, d)
