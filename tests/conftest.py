@@ -19,8 +19,8 @@ def golden_dir():
 
 def pytest_terminal_summary(terminalreporter, exitstatus, config):
     """Margins of the parity gate: for every test that compared against the oracle, the worst error under the
-    asserted floor and under tighter ones (see tests/util.py).  Also written to gpurun_out/parity_margins.txt
-    when that folder exists."""
+    asserted floor and under tighter ones (see tests/util.py).  Also written to the file named by the environment
+    variable PARITY_MARGINS_OUT, if set."""
     try:
         from tests.util import MARGINS
     except Exception:
@@ -35,7 +35,7 @@ def pytest_terminal_summary(terminalreporter, exitstatus, config):
     terminalreporter.write_sep("-", "parity margins (worst per test)")
     for l in lines:
         terminalreporter.write_line(l)
-    out = os.path.join(ROOT, "gpurun_out")
-    if os.path.isdir(out):
-        with open(os.path.join(out, "parity_margins.txt"), "w") as f:
+    out = os.environ.get("PARITY_MARGINS_OUT")
+    if out:
+        with open(out, "w") as f:
             f.write("\n".join(lines) + "\n")
