@@ -117,6 +117,9 @@ def main():
                     help="detag (default, the headline line); dsgt = the same kernels with K=1, eta=0; dpsgd = "
                          "detag_grad_quadratic_diag + detag_dpsgd_step.  The two baselines of the paper's "
                          "Experiments section, timed on the same workload")
+    ap.add_argument("--variant", default="atc", choices=["atc", "alg2"],
+                    help="phase update: atc (default; gradients enter before the gossip, the form the proof of "
+                         "Theorem 3 analyses) or alg2 (Algorithm 2 as printed: gossip first)")
     ap.add_argument("--dense", action="store_true",
                     help="run detag_step on DETAG_PATH_DENSE (the K rounds as one matrix-core product with the "
                          "polynomial p_K(W^T)); for the unfused step only, i.e. --config 5 or --unfused")
@@ -145,6 +148,11 @@ def main():
     n, d, K, alpha, sigma = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.sigma
     alg, what = args.algorithm, args.what
     per_round = args.path == "per_round"
+    variant = D.DETAG_VARIANT_ALG2 if args.variant == "alg2" else D.DETAG_VARIANT_ATC
+    VN = "ALG2" if args.variant == "alg2" else "ATC"
+    if args.variant != "atc" and (what != "step" or alg == "dpsgd"):
+        print("bench.py: --variant applies to --what step of detag and dsgt", file=sys.stderr)
+        sys.exit(2)
     if what != "step" and (alg != "detag" or args.dense or args.unfused):
         print("bench.py: --algorithm, --dense and --unfused apply to --what step", file=sys.stderr)
         sys.exit(2)
@@ -211,12 +219,12 @@ def main():
         elif fused:   # gradient query + phase in one kernel; Ga is the single gradient matrix, updated in place
             rec(0)
             ctx.step_quadratic(X, Y, state["Ga"], h, b, alpha, K, sigma=sigma, seed=cfg.seed, step=state["t"],
-                               eta=eta)
+                               eta=eta, variant=variant)
             rec(1)
         else:
             ctx.grad_quadratic_diag(X, h, b, state["Ga"], sigma=sigma, seed=cfg.seed, step=state["t"])
             rec(0)
-            ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K, eta)
+            ctx.step(X, Y, state["Ga"], state["Gb"], alpha, K, eta, variant)
             rec(1)
             state["Ga"], state["Gb"] = state["Gb"], state["Ga"]
         state["t"] += 1
@@ -263,7 +271,8 @@ def main():
                   + " (detag_dpsgd_step)")
     elif fused:
         bpe = 4 * sb + 12
-        kernel = "fused_quadratic_kernel (detag_step_quadratic)"
+        kernel = ("fused_quadratic_alg2_kernel" if args.variant == "alg2" else "fused_quadratic_kernel") + \
+            " (detag_step_quadratic)"
     elif per_round:
         bpe = 24 + 2 * rounds_bytes
         kernel = "elementwise_kernel + %s x%d (detag_step, one launch per round)" % (
@@ -287,16 +296,17 @@ def main():
     step_name = {"gossip": "detag_gossip_accel on X", "stream": "detag_step with K = 0 (tracking and model update only)",
                  "diag": "detag_mean + detag_consensus_error"}.get(what) or (
         "detag_grad_quadratic_diag + detag_dpsgd_step" if alg == "dpsgd"
-        else "detag_step_quadratic (gradient query + ATC phase, one kernel)" if fused
-        else "detag_grad_quadratic_diag + detag_step (ATC, one product with p_K(W^T))" if args.dense
-        else "detag_grad_quadratic_diag + detag_step (ATC, one launch per gossip round)" if per_round
-        else "detag_grad_quadratic_diag + detag_step (ATC, fused K rounds)")
+        else "detag_step_quadratic (gradient query + %s phase, one kernel)" % VN if fused
+        else "detag_grad_quadratic_diag + detag_step (%s, one product with p_K(W^T))" % VN if args.dense
+        else "detag_grad_quadratic_diag + detag_step (%s, one launch per gossip round)" % VN if per_round
+        else "detag_grad_quadratic_diag + detag_step (%s, fused K rounds)" % VN)
     if what in ("step", "gossip"):
         metric, unit, value = "worker-param-gossip-rounds/s (n*d*K/s)", "worker-param-gossip-rounds/s", E * K / (dt / args.steps)
     else:
         metric, unit, value = "state elements per second (n*d/s)", "elements/s", E / (dt / args.steps)
     traffic, traffic_source = None, None
-    if args.config == 4 and alg == "detag" and what == "step" and not per_round and not args.dense:
+    if args.config == 4 and alg == "detag" and what == "step" and not per_round and not args.dense \
+            and args.variant == "atc":
         traffic = measured_traffic(fused)
         traffic_source = ("stored: profiles/%s (rocprofv3 FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), "
                           "valid while the kernel sources hash to the recorded value"

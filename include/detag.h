@@ -394,9 +394,11 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
                                        uint32_t step, float *G_dev, void *stream);
 
 /*
- * detag_grad_quadratic_diag followed by detag_step (ATC), as one kernel: the
+ * detag_grad_quadratic_diag followed by detag_step, as one kernel: the
  * gradient query of Algorithm 2 at the phase-start model and the phase update,
- *   G+ = h*(X - b) + sigma*z;  X+ = M(X - alpha*Y);  Y+ = M(Y + G+ - G).
+ *   G+ = h*(X - b) + sigma*z, then
+ *   DETAG_VARIANT_ATC : X+ = M(X - alpha*Y);       Y+ = M(Y + G+ - G)
+ *   DETAG_VARIANT_ALG2: X+ = M(X) - alpha*M(Y);    Y+ = M(Y) + G+ - G.
  * G_dev (fp32 n x ld) holds the previous gradient buffer g(k-1) on entry and
  * g(k) on return, so the caller keeps ONE gradient matrix and does not swap.
  * h_dev: fp32, length ld and shared by all workers (h_per_worker = 0), or
@@ -406,12 +408,12 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
  * turns it off).  Results are identical to the two separate calls.
  * Only for contexts on a ring or 2-D torus with a register-resident kernel and
  * K >= 1 (DETAG_EUNSUPPORTED otherwise).  X, Y, G, h, b must not overlap.
- * Algorithm 2 as printed (DETAG_VARIANT_ALG2) has no one-kernel form: use the
- * two separate calls.
+ * Both variants move the same bytes (read X, Y, G, b; write X, Y, G); ALG2
+ * keeps the new gradient in LDS (n KiB per block) across the rounds.
  */
 detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
                                   int32_t h_per_worker, const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
-                                  int32_t K, double eta, void *stream);
+                                  int32_t K, double eta, int32_t variant /* detag_variant */, void *stream);
 
 /*
  * Gradient of f_i(x) = 1/2 ||A_i x - b_i||^2:  G[i,:] = A_i^T (A_i X[i,:] - b_i).

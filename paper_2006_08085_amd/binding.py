@@ -127,7 +127,7 @@ def lib() -> C.CDLL:
     L.detag_consensus_error_static.restype = C.c_int
     L.detag_grad_quadratic_diag.argtypes = [vp, vp, vp, i32, vp, vp, f32, u64, u32, vp, vp]
     L.detag_grad_quadratic_diag.restype = C.c_int
-    L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, i32, vp, f32, u64, u32, f64, i32, f64, vp]
+    L.detag_step_quadratic.argtypes = [vp, vp, vp, vp, vp, i32, vp, f32, u64, u32, f64, i32, f64, i32, vp]
     L.detag_step_quadratic.restype = C.c_int
     L.detag_grad_lstsq.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     L.detag_grad_lstsq.restype = C.c_int
@@ -445,7 +445,7 @@ class Context:
                                                     self._mat(G, torch.float32, "G"), self._stream()))
 
     def step_quadratic(self, X, Y, G, h, b, alpha: float, K: int, sigma: float = 0.0, seed: int = 0, step: int = 0,
-                       eta: float = -1.0):
+                       eta: float = -1.0, variant: int = DETAG_VARIANT_ATC):
         """h: a float32 vector of length >= d shared by the workers, or an n x ld matrix with one row per worker."""
         import torch
         per_worker = 1 if h.dim() == 2 else 0
@@ -458,7 +458,7 @@ class Context:
         self._check(lib().detag_step_quadratic(self._h, self._state(X, "X"), self._state(Y, "Y"),
                                                self._mat(G, torch.float32, "G"), hp, per_worker,
                                                self._mat(b, torch.float32, "b"), sigma, seed, step, alpha, K, eta,
-                                               self._stream()))
+                                               variant, self._stream()))
 
     def grad_lstsq(self, X, A, b, G):
         import torch
@@ -536,8 +536,9 @@ def detag_consensus_error(ctx: Context, X, out=None): return ctx.consensus_error
 def detag_consensus_error_static(ctx: Context, X, out): return ctx.consensus_error_static(X, out)
 def detag_grad_quadratic_diag(ctx: Context, X, h, b, G, noise=None, sigma=0.0, seed=0, step=0):
     ctx.grad_quadratic_diag(X, h, b, G, noise, sigma, seed, step)
-def detag_step_quadratic(ctx: Context, X, Y, G, h, b, alpha, K, sigma=0.0, seed=0, step=0, eta=-1.0):
-    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma, seed, step, eta)
+def detag_step_quadratic(ctx: Context, X, Y, G, h, b, alpha, K, sigma=0.0, seed=0, step=0, eta=-1.0,
+                         variant=DETAG_VARIANT_ATC):
+    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma, seed, step, eta, variant)
 def detag_grad_lstsq(ctx: Context, X, A, b, G): ctx.grad_lstsq(X, A, b, G)
 def detag_grad_softmax_bf16(ctx: Context, X, feats, labels, batch, C_classes, G, loss=None):
     ctx.grad_softmax_bf16(X, feats, labels, batch, C_classes, G, loss)

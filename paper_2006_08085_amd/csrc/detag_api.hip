@@ -800,8 +800,10 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
 
 detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
                                   int32_t h_per_worker, const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,
-                                  int32_t K, double eta, void *stream) {
+                                  int32_t K, double eta, int32_t variant, void *stream) {
   if (detag_status st = need_device(ctx)) return st;
+  if (variant != DETAG_VARIANT_ATC && variant != DETAG_VARIANT_ALG2)
+    return set_err(ctx, DETAG_EINVAL, "variant must be DETAG_VARIANT_ATC or DETAG_VARIANT_ALG2");
   if (detag_status st = check_state_ptr(ctx, X_dev, "X_dev")) return st;
   if (detag_status st = check_state_ptr(ctx, Y_dev, "Y_dev")) return st;
   if (detag_status st = check_f32_ptr(ctx, G_dev, "G_dev")) return st;
@@ -818,8 +820,8 @@ detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, floa
   if (K < 1 || !fused_structured_available(ctx->W) || ctx->path == DETAG_PATH_PER_ROUND)
     return set_err(ctx, DETAG_EUNSUPPORTED,
                    "detag_step_quadratic needs K >= 1 and a ring/torus context with a register-resident kernel");
-  const int rc = launch_fused_quadratic(ctx->shape, ctx->W, X_dev, Y_dev, G_dev, h_dev, h_per_worker != 0, b_dev, float(alpha), K, e,
-                                        sigma, seed, step, stream);
+  const int rc = launch_fused_quadratic(ctx->shape, ctx->W, variant == DETAG_VARIANT_ALG2, X_dev, Y_dev, G_dev, h_dev,
+                                        h_per_worker != 0, b_dev, float(alpha), K, e, sigma, seed, step, stream);
   return rc ? hip_fail(ctx, "fused gradient + phase", rc) : DETAG_OK;
 }
 

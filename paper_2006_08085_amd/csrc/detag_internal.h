@@ -125,8 +125,9 @@ bool fused_structured_available(const HostW &W);
 int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, void *Y, const float *Gn,
                             const float *Go, float alpha, int K, float eta, void *stream);
 // Gradient query of the diagonal quadratic + ATC phase in one kernel; G holds g(k-1) on entry, g(k) on exit.
-int launch_fused_quadratic(const Shape &s, const HostW &W, void *X, void *Y, float *G, const float *h, bool h_per_worker,
-                           const float *b, float alpha, int K, float eta, float sigma, uint64_t seed, uint32_t step, void *stream);
+int launch_fused_quadratic(const Shape &s, const HostW &W, bool alg2, void *X, void *Y, float *G, const float *h,
+                           bool h_per_worker, const float *b, float alpha, int K, float eta, float sigma, uint64_t seed,
+                           uint32_t step, void *stream);
 bool fused_generic_available(const HostW &W, const Shape &s);
 int launch_fused_generic(const Shape &s, const HostW &W, const DevCsr &w, int mode, void *X, void *Y,
                          const float *Gn, const float *Go, float alpha, int K, float eta, void *stream);

@@ -90,10 +90,12 @@ def test_config4_full_size_sampled_columns():
     assert (offset - offset0).abs().max().item() < 2e-5
 
 
-def test_config4_full_size_single_kernel_step():
-    """The entry point bench.py times by default (gradient query + phase in one kernel) at full size: one step
-    from a mid-run state against the oracle on sampled columns, and bit for bit against the two separate
-    kernels on the same inputs."""
+@pytest.mark.parametrize("variant", ["atc", "alg2"])
+def test_config4_full_size_single_kernel_step(variant):
+    """The entry point bench.py times by default (gradient query + phase in one kernel; ATC there, Algorithm 2 as
+    printed with --variant alg2) at full size: one step from a mid-run state against the oracle on sampled
+    columns, and bit for bit against the two separate kernels on the same inputs."""
+    var = D.DETAG_VARIANT_ATC if variant == "atc" else D.DETAG_VARIANT_ALG2
     cfg = CONFIGS[4]
     n, d, K, alpha, sigma, seed = cfg.n, cfg.d, cfg.K, cfg.lr, cfg.sigma, cfg.seed
     ld = D.padded_ld(d)
@@ -114,16 +116,16 @@ def test_config4_full_size_single_kernel_step():
     hs = h[idx].double().cpu().numpy()
     X2, Y2, Gold2 = X.clone(), Y.clone(), G.clone()
     step = 7
-    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma=sigma, seed=seed, step=step)
+    ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma=sigma, seed=seed, step=step, variant=var)
     Gns = OO.grad_quadratic_diag(Xs, hs, bs, ON.normal_noise(seed, step, n, cols), sigma)
-    Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
+    Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta, variant)
     S = amax(Xs, Ys, Gns, Gos)
     assert rel_err(take(G), Gns, S, floor=TIGHT) < TOL_F32
     assert rel_err(take(X), Xr, S, floor=TIGHT) < TOL_F32
     assert rel_err(take(Y), Yr, S, floor=TIGHT) < TOL_F32
     Gnew2 = D.new_matrix(n, d, ld, device=dev)
     ctx.grad_quadratic_diag(X2, h, b, Gnew2, sigma=sigma, seed=seed, step=step)
-    ctx.step(X2, Y2, Gnew2, Gold2, alpha, K)
+    ctx.step(X2, Y2, Gnew2, Gold2, alpha, K, variant=var)
     torch.cuda.synchronize()
     assert torch.equal(X, X2) and torch.equal(Y, Y2) and torch.equal(G, Gnew2)
 

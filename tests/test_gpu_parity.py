@@ -443,9 +443,11 @@ def test_config5_shape_bf16_short_run():
 @pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 16), ("torus48", 32), ("torus88", 64), ("ring", 64)])
 @pytest.mark.parametrize("sigma", [0.0, 0.1])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma, dtype):
+@pytest.mark.parametrize("variant", ["atc", "alg2"])
+def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma, dtype, variant):
     d, ld, K, alpha, seed = 777, 832, 5, 0.5, 99
     bf = dtype == "bf16"
+    var = D.DETAG_VARIANT_ATC if variant == "atc" else D.DETAG_VARIANT_ALG2
     tdt = torch.bfloat16 if bf else torch.float32
     ctx, W = make_ctx(kind, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
     eta = eta_for(W)
@@ -462,15 +464,15 @@ def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma
     Xs, Ys, Gos, Gns = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld), to_dev(np.zeros((n, d)), ld)
     Xr, Yr, Gor = X.astype(np.float64), Y.astype(np.float64), Go.astype(np.float64)
     for t in range(2):
-        ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=t)
+        ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=t, variant=var)
         ctx.grad_quadratic_diag(Xs, hd, bd, Gns, sigma=sigma, seed=seed, step=t)
-        ctx.step(Xs, Ys, Gns, Gos, alpha, K)
+        ctx.step(Xs, Ys, Gns, Gos, alpha, K, variant=var)
         Gos, Gns = Gns, Gos
         noise = ON.normal_noise(seed, t, n, cols) if sigma else None
         Gn = OO.grad_quadratic_diag(Xr, h, b, noise, sigma)
         if t == 0:
             S = amax(Xr, Yr, Gn, Gor)
-            Xn, Yn = OG.detag_step(Xr, Yr, Gn, Gor, W, alpha, K, eta)
+            Xn, Yn = OG.detag_step(Xr, Yr, Gn, Gor, W, alpha, K, eta, variant)
             tol = TOL_BF16 if bf else TOL_F32
             assert rel_err(to_host(Gf, d), Gn, S) < TOL_F32
             assert rel_err(to_host(Xf, d), Xn, S) < tol
@@ -496,6 +498,9 @@ def test_step_quadratic_unsupported_cases_are_statuses():
     assert ei.value.status == D.DETAG_EUNSUPPORTED
     with pytest.raises(D.DetagError) as ei:
         ctx2.step_quadratic(X, X, Gm, h, b, 0.1, 2)
+    assert ei.value.status == D.DETAG_EINVAL
+    with pytest.raises(D.DetagError) as ei:
+        ctx2.step_quadratic(X, Y, Gm, h, b, 0.1, 2, variant=7)
     assert ei.value.status == D.DETAG_EINVAL
 
 
@@ -549,11 +554,13 @@ def test_one_round_with_lds_staged_tile(n, graph, dtype, pad):
 
 @pytest.mark.parametrize("kind,n", [("ring", 16), ("torus88", 64)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_step_quadratic_with_per_worker_curvature(kind, n, dtype):
+@pytest.mark.parametrize("variant", ["atc", "alg2"])
+def test_step_quadratic_with_per_worker_curvature(kind, n, dtype, variant):
     """h as an n x ld matrix (every worker its own curvature): against the oracle and bit for bit against
     detag_grad_quadratic_diag + detag_step on the same inputs."""
     d, ld, K, alpha, sigma, seed = 700, 704, 4, 0.4, 0.1, 7
     bf = dtype == "bf16"
+    var = D.DETAG_VARIANT_ATC if variant == "atc" else D.DETAG_VARIANT_ALG2
     tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
     ctx, W = make_ctx(kind, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
     eta = eta_for(W)
@@ -565,11 +572,11 @@ def test_step_quadratic_with_per_worker_curvature(kind, n, dtype):
     hd, bd = to_dev(h, ld), to_dev(b, ld)
     Xf, Yf, Gf = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld)
     Xs, Ys, Gos, Gns = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld), to_dev(np.zeros((n, d)), ld)
-    ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=2)
+    ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=2, variant=var)
     ctx.grad_quadratic_diag(Xs, hd, bd, Gns, sigma=sigma, seed=seed, step=2)
-    ctx.step(Xs, Ys, Gns, Gos, alpha, K)
+    ctx.step(Xs, Ys, Gns, Gos, alpha, K, variant=var)
     Gn = OO.grad_quadratic_diag(X, h, b, ON.normal_noise(seed, 2, n, np.arange(d)), sigma)
-    Xn, Yn = OG.detag_step(X, Y, Gn, Go, W, alpha, K, eta)
+    Xn, Yn = OG.detag_step(X, Y, Gn, Go, W, alpha, K, eta, variant)
     S = amax(X, Y, Gn, Go)
     assert rel_err(to_host(Gf, d), Gn, S) < TOL_F32
     assert rel_err(to_host(Xf, d), Xn, S) < tol and rel_err(to_host(Yf, d), Yn, S) < tol
