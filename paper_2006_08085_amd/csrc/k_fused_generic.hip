@@ -44,9 +44,13 @@ struct RowTab {
   __device__ __forceinline__ float val(int k) const { return __uint_as_float(w[DEG / 2 + (UNI ? 0 : k)]); }
 };
 
-// One round for this lane's rows: v <- cm * sum_k W_ji (lds[j] - z) + eta * v;  z <- z + v;  then publish z.
+// One round for this lane's rows, with the velocity kept divided by (1+eta) (and, for rows whose neighbour
+// weights are all equal, also by that weight; the table then holds (1+eta)*weight, see scale_uniform_weights):
+//   u <- sum_k W_ji (lds[j] - z) + eta * u;   z <- z + (1+eta) * u;   then publish z.
+// Two multiplications fewer per output and round than with the velocity itself; the kernel issues about as many
+// vector-ALU cycles as LDS cycles per round, so they count.
 template <int DEG, bool UNI, bool FIRST>
-__device__ __forceinline__ void round_step(float (&z)[kRpt], float (&v)[kRpt], const char *lds_b, float *lds, int w,
+__device__ __forceinline__ void round_step(float (&z)[kRpt], float (&u)[kRpt], const char *lds_b, float *lds, int w,
                                            int lane, RowTab<DEG, UNI> (&tab)[kRpt], float cm, float eta) {
   // The packed offset words are made opaque once per round: otherwise their 16-bit halves are unpacked ahead
   // of the round loop into 4*DEG*... scalar registers of their own, which do not fit beside the table at two
@@ -69,24 +73,35 @@ __device__ __forceinline__ void round_step(float (&z)[kRpt], float (&v)[kRpt], c
       for (int len = DEG / 2; len >= 1; len /= 2)
 #pragma unroll
         for (int k = 0; k < len; ++k) s[k] += s[k + len];
-      acc = tab[r].val(0) * fmaf(-float(DEG), z[r], s[0]);
+      acc = fmaf(-float(DEG), z[r], s[0]);
     } else {
       acc = 0.f;
 #pragma unroll
       for (int k = 0; k < DEG; ++k) acc = fmaf(tab[r].val(k), nb(r, k) - z[r], acc);
     }
-    v[r] = FIRST ? cm * acc : fmaf(cm, acc, eta * v[r]);
+    u[r] = FIRST ? acc : fmaf(eta, u[r], acc);
   }
   __syncthreads();  // every read of z_r is done
 #pragma unroll
   for (int r = 0; r < kRpt; ++r) {
-    z[r] += v[r];
+    z[r] = fmaf(UNI ? tab[r].val(0) : cm, u[r], z[r]);
     lds[(w + kWaves * r) * kCols + lane] = z[r];
   }
   __syncthreads();  // z_{r+1} is visible
 }
 
-// K >= 1 rounds from z_{-1} = z_0 = z.  Result in z; v is scratch.
+// For rows with one weight, the table's weight word becomes (1+eta)*weight, a wavefront-uniform value kept in a
+// scalar register like the weight it replaces.
+template <int DEG, bool UNI>
+__device__ __forceinline__ void scale_uniform_weights(RowTab<DEG, UNI> (&tab)[kRpt], float cm) {
+  if constexpr (UNI) {
+#pragma unroll
+    for (int r = 0; r < kRpt; ++r)
+      tab[r].w[DEG / 2] = __builtin_amdgcn_readfirstlane(__float_as_uint(cm * tab[r].val(0)));
+  }
+}
+
+// K >= 1 rounds from z_{-1} = z_0 = z.  Result in z; v is scratch.  The table's weights are already scaled.
 template <int DEG, bool UNI>
 __device__ __forceinline__ void gossip(float (&z)[kRpt], float (&v)[kRpt], float *lds, int w, int lane,
                                        RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
@@ -125,6 +140,7 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
   for (int r = 0; r < kRpt; ++r)
 #pragma unroll
     for (int q = 0; q < TS; ++q) tab[r].w[q] = table[(w * kRpt + r) * TS + q];
+  scale_uniform_weights<DEG, UNI>(tab, 1.f + eta);
   float cur[kRpt], prev[kRpt];
   auto row = [&](int r) { return w + kWaves * r; };
   // Loads and stores go four rows at a time with the scheduler fenced in between: left alone, the compiler
