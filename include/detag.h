@@ -178,7 +178,10 @@ detag_status detag_set_path(detag_ctx *ctx, int32_t path /* detag_path */);
  *     bytes, but the rounds run at LDS bandwidth: per phase about
  *     0.9 ms + K * 0.16 ms at n = 256, d = 1 M (bf16 state), where HBM alone
  *     would take 0.6 ms: 4 to 5 times the register family's time per byte
- *     at K = 16, on par with it at K = 1.
+ *     at K = 16, on par with it at K = 1.  A block has 16, 32, 64, 128 or
+ *     256 row slots (the smallest count that holds n), and its time goes with
+ *     the slots: a 1 GiB fp32 matrix takes 1.0-1.2 ms per 8-round gossip for
+ *     n = 24 ... 256, 1.7 ms for n = 12, 2.8 ms for n = 7.
  *   DETAG_KERNEL_PER_ROUND  everything else (n > 256, a worker with more than 8
  *     neighbours), or DETAG_PATH_PER_ROUND: one launch per round, 12 B per
  *     element and round (24 + 8*(3K-1) B per element and phase: 208 B at K = 8,

@@ -3,9 +3,10 @@
 // with Metropolis weights).
 //
 // A block of 16 wavefronts owns 64 columns and all n rows of them.  Wavefront w
-// owns the rows w, w+16, w+32, ... (16 of them); lane l owns column l.  Each lane
-// keeps z_r and the velocity z_r - z_{r-1} of its own 16 rows in registers; z_r
-// of ALL rows also sits in LDS (256 x 64 fp32), where the neighbours of a row
+// owns the rows w, w+16, w+32, ... (RPT of them, RPT = 1, 2, 4, 8 or 16 by the
+// number of workers); lane l owns column l.  Each lane
+// keeps z_r and the velocity z_r - z_{r-1} of its own rows in registers; z_r
+// of ALL rows also sits in LDS (16*RPT x 64 fp32), where the neighbours of a row
 // are read.  Row indices are wavefront-uniform:
 // the neighbour list of a row is a handful of scalars (16-bit LDS offsets packed
 // in pairs, the weights), read once per kernel, and every LDS access is 64
@@ -25,7 +26,17 @@
 namespace detag {
 namespace {
 
-constexpr int kWaves = 16, kThreads = 64 * kWaves, kCols = 64, kRpt = 16, kRowsMax = kWaves * kRpt;  // 256 rows
+constexpr int kWaves = 16, kThreads = 64 * kWaves, kCols = 64, RPTMax = 16, kRowsMax = kWaves * RPTMax;  // 256 rows
+
+// Rows per wavefront (RPT below): the smallest of 1, 2, 4, 8, 16 that gives all n workers a slot (16 * RPT >= n).
+// A block's arithmetic, LDS footprint and table are proportional to its slots, not to n, so a small graph on
+// the 256-slot layout would pay for 256 workers (measured on a 7-worker ring: 18 times the time per byte of the
+// 256-worker case).
+int rows_per_wave(int n) {
+  int r = 1;
+  while (r < RPTMax && kWaves * r < n) r *= 2;
+  return r;
+}
 
 // Table words per row: DEG/2 words of packed 16-bit LDS byte offsets, then the
 // neighbour weights (one word if they are all equal, else DEG).  W_ii is not
@@ -49,20 +60,20 @@ struct RowTab {
 //   u <- sum_k W_ji (lds[j] - z) + eta * u;   z <- z + (1+eta) * u;   then publish z.
 // Two multiplications fewer per output and round than with the velocity itself; the kernel issues about as many
 // vector-ALU cycles as LDS cycles per round, so they count.
-template <int DEG, bool UNI, bool FIRST>
-__device__ __forceinline__ void round_step(float (&z)[kRpt], float (&u)[kRpt], const char *lds_b, float *lds, int w,
-                                           int lane, RowTab<DEG, UNI> (&tab)[kRpt], float cm, float eta) {
+template <int DEG, bool UNI, bool FIRST, int RPT>
+__device__ __forceinline__ void round_step(float (&z)[RPT], float (&u)[RPT], const char *lds_b, float *lds, int w,
+                                           int lane, RowTab<DEG, UNI> (&tab)[RPT], float cm, float eta) {
   // The packed offset words are made opaque once per round: otherwise their 16-bit halves are unpacked ahead
   // of the round loop into 4*DEG*... scalar registers of their own, which do not fit beside the table at two
   // blocks per compute unit and end up spilled.
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r)
+  for (int r = 0; r < RPT; ++r)
 #pragma unroll
     for (int q = 0; q < DEG / 2; ++q) asm volatile("" : "+s"(tab[r].w[q]));
   const uint32_t lane4 = uint32_t(lane) * 4u;
   auto nb = [&](int r, int k) { return *reinterpret_cast<const float *>(lds_b + (tab[r].off(k) + lane4)); };
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r) {
+  for (int r = 0; r < RPT; ++r) {
     float acc;
     if constexpr (UNI) {
       // pairwise tree: DEG equal values sum exactly, so s - DEG*z is exactly zero for them
@@ -83,7 +94,7 @@ __device__ __forceinline__ void round_step(float (&z)[kRpt], float (&u)[kRpt], c
   }
   __syncthreads();  // every read of z_r is done
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r) {
+  for (int r = 0; r < RPT; ++r) {
     z[r] = fmaf(UNI ? tab[r].val(0) : cm, u[r], z[r]);
     lds[(w + kWaves * r) * kCols + lane] = z[r];
   }
@@ -92,26 +103,26 @@ __device__ __forceinline__ void round_step(float (&z)[kRpt], float (&u)[kRpt], c
 
 // For rows with one weight, the table's weight word becomes (1+eta)*weight, a wavefront-uniform value kept in a
 // scalar register like the weight it replaces.
-template <int DEG, bool UNI>
-__device__ __forceinline__ void scale_uniform_weights(RowTab<DEG, UNI> (&tab)[kRpt], float cm) {
+template <int DEG, bool UNI, int RPT>
+__device__ __forceinline__ void scale_uniform_weights(RowTab<DEG, UNI> (&tab)[RPT], float cm) {
   if constexpr (UNI) {
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r)
+    for (int r = 0; r < RPT; ++r)
       tab[r].w[DEG / 2] = __builtin_amdgcn_readfirstlane(__float_as_uint(cm * tab[r].val(0)));
   }
 }
 
 // K >= 1 rounds from z_{-1} = z_0 = z.  Result in z; v is scratch.  The table's weights are already scaled.
-template <int DEG, bool UNI>
-__device__ __forceinline__ void gossip(float (&z)[kRpt], float (&v)[kRpt], float *lds, int w, int lane,
-                                       RowTab<DEG, UNI> (&tab)[kRpt], float eta, int K) {
+template <int DEG, bool UNI, int RPT>
+__device__ __forceinline__ void gossip(float (&z)[RPT], float (&v)[RPT], float *lds, int w, int lane,
+                                       RowTab<DEG, UNI> (&tab)[RPT], float eta, int K) {
   const float cm = 1.f + eta;
   const char *lds_b = reinterpret_cast<const char *>(lds);
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r) lds[(w + kWaves * r) * kCols + lane] = z[r];
+  for (int r = 0; r < RPT; ++r) lds[(w + kWaves * r) * kCols + lane] = z[r];
   __syncthreads();
-  round_step<DEG, UNI, true>(z, v, lds_b, lds, w, lane, tab, cm, eta);
-  for (int r = 1; r < K; ++r) round_step<DEG, UNI, false>(z, v, lds_b, lds, w, lane, tab, cm, eta);
+  round_step<DEG, UNI, true, RPT>(z, v, lds_b, lds, w, lane, tab, cm, eta);
+  for (int r = 1; r < K; ++r) round_step<DEG, UNI, false, RPT>(z, v, lds_b, lds, w, lane, tab, cm, eta);
 }
 
 // Window of row i of the tile; rows >= n get an empty window (loads give 0, stores are dropped).
@@ -122,12 +133,12 @@ __device__ __forceinline__ rsrc_t win(const E *base, int64_t tile, int64_t ld, i
 
 // mode 0: Z <- M(Z) on X.  mode 1 (ATC): X <- M(X - alpha*Y), Y <- M(Y + Gn - Go).
 // mode 2 (ALG2): X <- M(X) - alpha*M(Y), Y <- M(Y) + Gn - Go.
-template <typename ST, int DEG, bool UNI, int MODE>
+template <typename ST, int DEG, bool UNI, int MODE, int RPT>
 __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y, const float *__restrict__ Gn,
                                                                     const float *__restrict__ Go, int n, int64_t d,
                                                                     int64_t ld, const uint32_t *__restrict__ table,
                                                                     float eta, float alpha, int K) {
-  extern __shared__ float lds[];  // 256 x 64
+  extern __shared__ float lds[];  // 16*RPT x 64
   // the wavefront index is uniform: say so, or the row indices and with them every
   // table access are treated as per-lane values
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -135,34 +146,34 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
   const uint32_t valid = uint32_t(d - tile < kCols ? d - tile : kCols);
   const uint32_t so = lane * uint32_t(sizeof(ST)), fo = lane * 4u;
   constexpr int TS = table_stride(DEG, UNI);
-  RowTab<DEG, UNI> tab[kRpt];
+  RowTab<DEG, UNI> tab[RPT];
 #pragma unroll
-  for (int r = 0; r < kRpt; ++r)
+  for (int r = 0; r < RPT; ++r)
 #pragma unroll
-    for (int q = 0; q < TS; ++q) tab[r].w[q] = table[(w * kRpt + r) * TS + q];
-  scale_uniform_weights<DEG, UNI>(tab, 1.f + eta);
-  float cur[kRpt], prev[kRpt];
+    for (int q = 0; q < TS; ++q) tab[r].w[q] = table[(w * RPT + r) * TS + q];
+  scale_uniform_weights<DEG, UNI, RPT>(tab, 1.f + eta);
+  float cur[RPT], prev[RPT];
   auto row = [&](int r) { return w + kWaves * r; };
   // Loads and stores go four rows at a time with the scheduler fenced in between: left alone, the compiler
   // issues all 16 rows' loads of every array at once, and the registers they hold decide how many blocks
   // fit on a compute unit.  Two blocks per unit is what lets one block's memory phases run under the
   // other's rounds.
-  constexpr int kBatch = 4;
+  constexpr int kBatch = RPT < 4 ? RPT : 4;
   if constexpr (MODE == 0) {
 #pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+    for (int r0 = 0; r0 < RPT; r0 += kBatch) {
 #pragma unroll
       for (int r = r0; r < r0 + kBatch; ++r) cur[r] = buf_load<ST>(win(X, tile, ld, row(r), n, valid), so);
       __builtin_amdgcn_sched_barrier(0);
     }
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+    gossip<DEG, UNI, RPT>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
+    for (int r = 0; r < RPT; ++r) buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
   } else if constexpr (MODE == 1) {
     // every input is read once: the second gossip's input Y + Gn - Go waits in registers under the first
-    float v0[kRpt];
+    float v0[RPT];
 #pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+    for (int r0 = 0; r0 < RPT; r0 += kBatch) {
       float x[kBatch], y[kBatch], gn[kBatch], go[kBatch];
 #pragma unroll
       for (int q = 0; q < kBatch; ++q) {
@@ -179,28 +190,28 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+    gossip<DEG, UNI, RPT>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) {
+    for (int r = 0; r < RPT; ++r) {
       buf_store<ST>(win(X, tile, ld, row(r), n, valid), so, cur[r]);
       cur[r] = v0[r];
     }
     __builtin_amdgcn_sched_barrier(0);
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+    gossip<DEG, UNI, RPT>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r = 0; r < kRpt; ++r) buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so, cur[r]);
+    for (int r = 0; r < RPT; ++r) buf_store<ST>(win(Y, tile, ld, row(r), n, valid), so, cur[r]);
   } else {
     // M(Y) first: both outputs need it
 #pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+    for (int r0 = 0; r0 < RPT; r0 += kBatch) {
 #pragma unroll
       for (int r = r0; r < r0 + kBatch; ++r) cur[r] = buf_load<ST>(win(Y, tile, ld, row(r), n, valid), so);
       __builtin_amdgcn_sched_barrier(0);
     }
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
-    float v[kRpt];
+    gossip<DEG, UNI, RPT>(cur, prev, lds, w, lane, tab, eta, K);
+    float v[RPT];
 #pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+    for (int r0 = 0; r0 < RPT; r0 += kBatch) {
 #pragma unroll
       for (int r = r0; r < r0 + kBatch; ++r) {
         v[r] = cur[r];
@@ -208,9 +219,9 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    gossip<DEG, UNI>(cur, prev, lds, w, lane, tab, eta, K);
+    gossip<DEG, UNI, RPT>(cur, prev, lds, w, lane, tab, eta, K);
 #pragma unroll
-    for (int r0 = 0; r0 < kRpt; r0 += kBatch) {
+    for (int r0 = 0; r0 < RPT; r0 += kBatch) {
       float gn[kBatch], go[kBatch];
 #pragma unroll
       for (int q = 0; q < kBatch; ++q) {
@@ -227,30 +238,40 @@ __global__ __launch_bounds__(kThreads, 8) void fused_generic_kernel(ST *X, ST *Y
   }
 }
 
+template <typename ST, int DEG, bool UNI, int RPT>
+int launch_r(const Shape &s, const uint32_t *table, int mode, void *X, void *Y, const float *Gn, const float *Go,
+             float alpha, int K, float eta, void *stream) {
+  const dim3 grid(ceil_div_i64(s.d, kCols));
+  const size_t lds_bytes = size_t(kWaves) * RPT * kCols * sizeof(float);  // 4 KiB per row of a wavefront
+  auto st = static_cast<hipStream_t>(stream);
+  ST *x = static_cast<ST *>(X), *y = static_cast<ST *>(Y);
+#define DETAG_MODE(M)                                                                                             \
+  fused_generic_kernel<ST, DEG, UNI, M, RPT><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, \
+                                                                                eta, alpha, K)
+  switch (mode) {
+    case 0: DETAG_MODE(0); break;
+    case 1: DETAG_MODE(1); break;
+    case 2: DETAG_MODE(2); break;
+    default: return hip_rc(hipErrorInvalidValue);
+  }
+#undef DETAG_MODE
+  return hip_rc(hipGetLastError());
+}
+
 template <typename ST, int DEG, bool UNI>
 int launch_k(const Shape &s, const uint32_t *table, int mode, void *X, void *Y, const float *Gn, const float *Go,
              float alpha, int K, float eta, void *stream) {
-  const dim3 grid(ceil_div_i64(s.d, kCols));
-  const size_t lds_bytes = size_t(kRowsMax) * kCols * sizeof(float);  // 64 KiB
-  auto st = static_cast<hipStream_t>(stream);
-  ST *x = static_cast<ST *>(X), *y = static_cast<ST *>(Y);
-  switch (mode) {
-    case 0:
-      fused_generic_kernel<ST, DEG, UNI, 0><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
-                                                                              alpha, K);
-      break;
-    case 1:
-      fused_generic_kernel<ST, DEG, UNI, 1><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
-                                                                              alpha, K);
-      break;
-    case 2:
-      fused_generic_kernel<ST, DEG, UNI, 2><<<grid, kThreads, lds_bytes, st>>>(x, y, Gn, Go, s.n, s.d, s.ld, table, eta,
-                                                                              alpha, K);
-      break;
-    default:
-      return hip_rc(hipErrorInvalidValue);
+#define DETAG_RPT(R) \
+  case R: return launch_r<ST, DEG, UNI, R>(s, table, mode, X, Y, Gn, Go, alpha, K, eta, stream)
+  switch (rows_per_wave(s.n)) {
+    DETAG_RPT(1);
+    DETAG_RPT(2);
+    DETAG_RPT(4);
+    DETAG_RPT(8);
+    DETAG_RPT(16);
   }
-  return hip_rc(hipGetLastError());
+#undef DETAG_RPT
+  return -1;
 }
 
 template <typename ST>
@@ -299,9 +320,10 @@ bool build_ell(const HostW &W, EllHost &out) {
   out.deg = maxdeg <= 2 ? 2 : maxdeg <= 4 ? 4 : 8;
   out.uniform = uniform;
   const int ts = table_stride(out.deg, uniform);
-  out.table.assign(size_t(kRowsMax) * ts, 0u);
-  for (int i = 0; i < kRowsMax; ++i) {
-    uint32_t *t = &out.table[size_t((i % kWaves) * kRpt + i / kWaves) * ts];
+  const int rpt = rows_per_wave(n), slots = kWaves * rpt;
+  out.table.assign(size_t(slots) * ts, 0u);
+  for (int i = 0; i < slots; ++i) {
+    uint32_t *t = &out.table[size_t((i % kWaves) * rpt + i / kWaves) * ts];
     const uint32_t own = uint32_t(i) * kCols * 4u;  // byte offset of row i in LDS (< 65536)
     uint32_t offs[8];
     float vals[8];

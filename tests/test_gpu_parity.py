@@ -368,7 +368,9 @@ def test_wide_rows_fall_back_to_the_per_round_path():
 
 
 @pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (61, "irregular"), (100, "irregular"), (130, "rr"), (256, "rr"),
-                                     (1, "ring"), (2, "ring"), (3, "ring"), (17, "ring")])   # degenerate and odd rings
+                                     (1, "ring"), (2, "ring"), (3, "ring"), (17, "ring"),    # degenerate and odd rings
+                                     # worker counts at and just past a full set of row slots (16 wavefronts x 1, 2, 4, 8 rows)
+                                     (16, "rr"), (33, "irregular"), (64, "rr"), (128, "rr"), (129, "irregular")])
 @pytest.mark.parametrize("K", [1, 2, 5, 16])
 def test_generic_fused_gossip_and_step(n, graph, K):
     d, ld = 150, 160               # two full 64-column tiles and a ragged one
