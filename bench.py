@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=[2, 4, 5],
                     help="4 (default) is the headline workload; 2 and 5 are the other quadratic workloads "
-                         "(5: n=256 random 4-regular graph, bf16 state, K=16, runs as gradient kernel + phase kernel)")
+                         "(5: n=256 random 4-regular graph, bf16 state, K=16, on the LDS-resident kernels)")
     ap.add_argument("--what", default="step", choices=["step", "gossip", "stream", "diag"],
                     help="what one timed step is: the whole hot path (default), detag_gossip_accel alone, the "
                          "elementwise update without gossip (K = 0), or the two diagnostics")
@@ -122,7 +122,7 @@ def main():
                          "Theorem 3 analyses) or alg2 (Algorithm 2 as printed: gossip first)")
     ap.add_argument("--dense", action="store_true",
                     help="run detag_step on DETAG_PATH_DENSE (the K rounds as one matrix-core product with the "
-                         "polynomial p_K(W^T)); for the unfused step only, i.e. --config 5 or --unfused")
+                         "polynomial p_K(W^T)); implies --unfused")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of one n x ld fp32 matrix (a kernel of known "
                          "traffic, for scaling profiler byte counters); untimed")
@@ -184,10 +184,12 @@ def main():
     ce_out = torch.zeros(1, dtype=torch.float64, device=dev)
 
     state = {"t": 0, "Ga": Ga, "Gb": Gb}
-    fused = what == "step" and not args.unfused and not per_round and alg != "dpsgd" and structured
+    # one kernel for gradient query + phase: both variants on ring and torus, ATC for any other on-chip context
+    fused = what == "step" and not args.unfused and not per_round and alg != "dpsgd" and not args.dense and \
+        (structured or args.variant == "atc")
     if args.dense:
         if fused or alg == "dpsgd" or per_round:
-            print("bench.py: --dense applies to the two-kernel step (--config 5, or --unfused)", file=sys.stderr)
+            print("bench.py: --dense applies to the two-kernel step of detag and dsgt, timed as launches", file=sys.stderr)
             sys.exit(2)
         ctx.set_path(D.DETAG_PATH_DENSE)
     if what != "step":                                # a non-trivial state for the partial paths
@@ -271,8 +273,10 @@ def main():
                   + " (detag_dpsgd_step)")
     elif fused:
         bpe = 4 * sb + 12
-        kernel = ("fused_quadratic_alg2_kernel" if args.variant == "alg2" else "fused_quadratic_kernel") + \
-            " (detag_step_quadratic)"
+        kernel = ("fused_generic_quadratic_kernel" if not structured else "fused_quadratic_alg2_kernel"
+                  if args.variant == "alg2" else "fused_quadratic_kernel") + " (detag_step_quadratic)"
+        if not structured:
+            note = "this kernel keeps all rows of a tile in LDS and is bound by LDS bandwidth and VALU issue, not by HBM"
     elif per_round:
         bpe = 24 + 2 * rounds_bytes
         kernel = "elementwise_kernel + %s x%d (detag_step, one launch per round)" % (

@@ -171,8 +171,8 @@ detag_status detag_set_path(detag_ctx *ctx, int32_t path /* detag_path */);
  *     4x8, 8x8 (built from DETAG_TOPO_RING / DETAG_TOPO_TORUS2D with uniform
  *     weights and any kappa).  All n rows of a column in registers, K rounds
  *     on chip: 24 B per element and phase whatever K is, 0.66 of HBM peak at
- *     n = 64, d = 11.2 M.  Only this family serves detag_step_quadratic and
- *     the one-pass detag_dpsgd_step.
+ *     n = 64, d = 11.2 M.  Only this family serves detag_step_quadratic with
+ *     DETAG_VARIANT_ALG2 and the one-pass detag_dpsgd_step.
  *   DETAG_KERNEL_LDS_TILE  any other W with n <= 256 and at most 8 neighbours
  *     per worker, including rings and tori off the list above.  Same HBM
  *     bytes, but the rounds run at LDS bandwidth: per phase about
@@ -409,10 +409,14 @@ detag_status detag_grad_quadratic_diag(detag_ctx *ctx, const void *X_dev, const 
  * b_dev: fp32 n x ld; noise is
  * always the counter-based generator of detag_grad_quadratic_diag (sigma = 0
  * turns it off).  Results are identical to the two separate calls.
- * Only for contexts on a ring or 2-D torus with a register-resident kernel and
- * K >= 1 (DETAG_EUNSUPPORTED otherwise).  X, Y, G, h, b must not overlap.
- * Both variants move the same bytes (read X, Y, G, b; write X, Y, G); ALG2
- * keeps the new gradient in LDS (n KiB per block) across the rounds.
+ * For contexts whose rounds run on chip and K >= 1 (DETAG_EUNSUPPORTED
+ * otherwise: per-round or dense path, n > 256, a worker with more than 8
+ * neighbours).  On the register-resident family (detag_get_kernel) both
+ * variants exist and move the same bytes (read X, Y, G, b; write X, Y, G);
+ * ALG2 keeps the new gradient in LDS (n KiB per block) across the rounds.  On
+ * the LDS-resident family only DETAG_VARIANT_ATC exists (its LDS holds the
+ * rows of the state; DETAG_EUNSUPPORTED for ALG2: use the two separate calls).
+ * X, Y, G, h, b must not overlap.
  */
 detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, float *G_dev, const float *h_dev,
                                   int32_t h_per_worker, const float *b_dev, float sigma, uint64_t seed, uint32_t step, double alpha,

@@ -817,11 +817,25 @@ detag_status detag_step_quadratic(detag_ctx *ctx, void *X_dev, void *Y_dev, floa
   if (!std::isfinite(alpha) || !std::isfinite(sigma)) return set_err(ctx, DETAG_EINVAL, "alpha and sigma must be finite");
   float e;
   if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
-  if (K < 1 || !fused_structured_available(ctx->W) || ctx->path == DETAG_PATH_PER_ROUND)
+  Chosen path = kPerRound;
+  if (K >= 1)
+    if (detag_status st = choose_path(ctx, &path)) return st;
+  if (path != kFusedStructured && path != kFusedGeneric)
     return set_err(ctx, DETAG_EUNSUPPORTED,
-                   "detag_step_quadratic needs K >= 1 and a ring/torus context with a register-resident kernel");
-  const int rc = launch_fused_quadratic(ctx->shape, ctx->W, variant == DETAG_VARIANT_ALG2, X_dev, Y_dev, G_dev, h_dev,
-                                        h_per_worker != 0, b_dev, float(alpha), K, e, sigma, seed, step, stream);
+                   "detag_step_quadratic needs K >= 1 and a context whose rounds run on chip (register-resident or "
+                   "LDS-resident kernels, not the per-round or dense path)");
+  int rc;
+  if (path == kFusedStructured) {
+    rc = launch_fused_quadratic(ctx->shape, ctx->W, variant == DETAG_VARIANT_ALG2, X_dev, Y_dev, G_dev, h_dev,
+                                h_per_worker != 0, b_dev, float(alpha), K, e, sigma, seed, step, stream);
+  } else {
+    if (variant != DETAG_VARIANT_ATC)
+      return set_err(ctx, DETAG_EUNSUPPORTED,
+                     "Algorithm 2 as printed in one kernel needs the register-resident family (ring or torus on its "
+                     "list); use detag_grad_quadratic_diag + detag_step");
+    rc = launch_fused_generic_quadratic(ctx->shape, dev_csr(ctx), X_dev, Y_dev, G_dev, h_dev, h_per_worker != 0, b_dev,
+                                        float(alpha), K, e, sigma, seed, step, stream);
+  }
   return rc ? hip_fail(ctx, "fused gradient + phase", rc) : DETAG_OK;
 }
 

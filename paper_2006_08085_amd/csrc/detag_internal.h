@@ -129,6 +129,9 @@ int launch_fused_quadratic(const Shape &s, const HostW &W, bool alg2, void *X, v
                            bool h_per_worker, const float *b, float alpha, int K, float eta, float sigma, uint64_t seed,
                            uint32_t step, void *stream);
 bool fused_generic_available(const HostW &W, const Shape &s);
+int launch_fused_generic_quadratic(const Shape &s, const DevCsr &w, void *X, void *Y, float *G, const float *h,
+                                   bool h_per_worker, const float *b, float alpha, int K, float eta, float sigma,
+                                   uint64_t seed, uint32_t step, void *stream);
 int launch_fused_generic(const Shape &s, const HostW &W, const DevCsr &w, int mode, void *X, void *Y,
                          const float *Gn, const float *Go, float alpha, int K, float eta, void *stream);
 

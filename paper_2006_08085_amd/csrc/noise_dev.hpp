@@ -53,4 +53,24 @@ __device__ __forceinline__ void normal4(uint64_t q, uint32_t worker, uint32_t st
   box_muller(r[2], r[3], z[2], z[3]);
 }
 
+// One Philox block yields the normals of four adjacent columns of one worker.  A kernel whose lanes own one
+// column each and walk the rows four at a time lets the four lanes of a quad (four adjacent columns) generate
+// the blocks of four consecutive rows, one each, and exchanges the results with two DPP quad permutes: a 4x4
+// transpose, so that every lane evaluates one block per four rows instead of four.
+template <int CTRL>
+__device__ __forceinline__ float quad_perm(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// a[k] = M[j][k] in quad lane j  ->  a[k] = M[k][j]
+__device__ __forceinline__ void quad_transpose(float (&a)[4], unsigned j) {
+  const bool odd = j & 1u, hi = j & 2u;
+  const float t0 = quad_perm<0xB1>(odd ? a[0] : a[1]);  // lanes j ^ 1
+  const float t1 = quad_perm<0xB1>(odd ? a[2] : a[3]);
+  const float c0 = odd ? t0 : a[0], c1 = odd ? a[1] : t0, c2 = odd ? t1 : a[2], c3 = odd ? a[3] : t1;
+  const float s0 = quad_perm<0x4E>(hi ? c0 : c2);       // lanes j ^ 2
+  const float s1 = quad_perm<0x4E>(hi ? c1 : c3);
+  a[0] = hi ? s0 : c0, a[1] = hi ? s1 : c1, a[2] = hi ? c2 : s0, a[3] = hi ? c3 : s1;
+}
+
 }  // namespace detag

@@ -167,10 +167,11 @@ def test_config2_full_run(path):
     _check_run(run, traj, zbar, cfg.T, cfg.sigma, step, grad_of, TOL_F32, 2e-6)
 
 
-@pytest.mark.parametrize("path", ["rounds", "dense"])
+@pytest.mark.parametrize("path", ["single_kernel", "rounds", "dense"])
 def test_config5_full_run(path):
     """n=256, the library's seeded random 4-regular graph with Metropolis weights, d=1,048,576, bf16 X and Y,
-    K=16, lr=0.5, all T=50 steps at full width: the K rounds on chip, and as one product with the gossip
+    K=16, lr=0.5, all T=50 steps at full width: gradient query and phase in one kernel (what bench.py --config 5
+    times), the two separate kernels with the K rounds on chip, and the phase as one product with the gossip
     polynomial."""
     cfg = CONFIGS[5]
     run = _QuadraticRun(cfg, D.Topology.random_regular(cfg.degree, cfg.seed), tile=64,
@@ -181,10 +182,14 @@ def test_config5_full_run(path):
     traj, zbar = run.oracle(cfg.T, 0.0)
     bufs = [D.new_matrix(run.n, run.d, run.ld, device=DEV) for _ in range(2)]
 
-    def step(t):
-        run.ctx.grad_quadratic_diag(run.X, run.h, run.b, bufs[0])
-        run.ctx.step(run.X, run.Y, bufs[0], bufs[1], cfg.lr, cfg.K)
-        bufs.reverse()
+    if path == "single_kernel":
+        def step(t):
+            run.ctx.step_quadratic(run.X, run.Y, bufs[1], run.h, run.b, cfg.lr, cfg.K)
+    else:
+        def step(t):
+            run.ctx.grad_quadratic_diag(run.X, run.h, run.b, bufs[0])
+            run.ctx.step(run.X, run.Y, bufs[0], bufs[1], cfg.lr, cfg.K)
+            bufs.reverse()
     # stored state is bf16: the identities hold up to the rounding of 256 stored values per column
     _check_run(run, traj, zbar, cfg.T, 0.0, step, lambda: bufs[1], TOL_BF16, 2.0 ** -9)
 

@@ -487,11 +487,22 @@ def test_step_quadratic_matches_oracle_and_the_two_separate_calls(kind, n, sigma
 
 
 def test_step_quadratic_unsupported_cases_are_statuses():
-    ctx, _ = make_ctx("rr", 12, 100, 128)
-    X, Y, Gm, b = (D.new_matrix(12, 100, 128) for _ in range(4))
+    n = 12
+    full = [(i, j) for i in range(n) for j in range(i + 1, n)]         # 11 neighbours per worker: no on-chip kernel
+    ctx = D.detag_create(D.Topology.from_edges(full, D.DETAG_W_METROPOLIS), n, 100, 128)
+    assert not ctx.has_fused()
+    X, Y, Gm, b = (D.new_matrix(n, 100, 128) for _ in range(4))
     h = torch.ones(128, device=DEV)
     with pytest.raises(D.DetagError) as ei:
         ctx.step_quadratic(X, Y, Gm, h, b, 0.1, 4)
+    assert ei.value.status == D.DETAG_EUNSUPPORTED
+    ctx1, _ = make_ctx("rr", 12, 100, 128)                            # LDS-resident family: ATC only
+    with pytest.raises(D.DetagError) as ei:
+        ctx1.step_quadratic(X, Y, Gm, h, b, 0.1, 4, variant=D.DETAG_VARIANT_ALG2)
+    assert ei.value.status == D.DETAG_EUNSUPPORTED
+    ctx1.set_path(D.DETAG_PATH_PER_ROUND)
+    with pytest.raises(D.DetagError) as ei:
+        ctx1.step_quadratic(X, Y, Gm, h, b, 0.1, 4)
     assert ei.value.status == D.DETAG_EUNSUPPORTED
     ctx2, _ = make_ctx("ring", 8, 100, 128)
     X, Y, Gm, b = (D.new_matrix(8, 100, 128) for _ in range(4))
@@ -504,6 +515,60 @@ def test_step_quadratic_unsupported_cases_are_statuses():
     with pytest.raises(D.DetagError) as ei:
         ctx2.step_quadratic(X, Y, Gm, h, b, 0.1, 2, variant=7)
     assert ei.value.status == D.DETAG_EINVAL
+
+
+@pytest.mark.parametrize("n,graph", [(5, "asym"), (12, "rr"), (17, "ring"), (33, "irregular"), (61, "irregular"),
+                                     (100, "irregular"), (128, "rr"), (256, "rr")])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("hkind", ["shared", "per_worker"])
+def test_step_quadratic_on_lds_resident_contexts(n, graph, dtype, hkind):
+    """Gradient query + ATC phase in one kernel for an arbitrary sparse W (every count of row slots per wavefront):
+    two steps against the oracle and bit for bit against detag_grad_quadratic_diag + detag_step."""
+    d, ld, K, alpha, sigma, seed = 150, 160, 5, 0.4, 0.1, 11           # two full 64-column tiles and a ragged one
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    if graph == "asym":
+        W = 0.5 * np.eye(n) + 0.5 * np.roll(np.eye(n), 1, axis=1)
+        topo = D.Topology.from_dense(W)
+    elif graph == "ring":
+        topo, W = D.Topology.ring(), OT.mixing_matrix(n, gen.edges_ring(n))
+    else:
+        e = gen.edges_random_regular(n, 4, seed=n) if graph == "rr" else _irregular_edges(n, seed=n)
+        topo, W = D.Topology.from_edges(e, D.DETAG_W_METROPOLIS), OT.mixing_matrix(n, e, "metropolis")
+    ctx = D.detag_create(topo, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    assert ctx.kernel() == D.DETAG_KERNEL_LDS_TILE
+    eta = 0.3 if graph == "asym" else eta_for(W)
+    h1, b = gen.quadratic_problem(n, d, seed=3)
+    if hkind == "per_worker":
+        h = np.exp(np.random.default_rng(5).uniform(np.log(1e-3), 0.0, size=(n, d))).astype(np.float32)
+        hd = to_dev(h, ld)
+    else:
+        h = h1
+        hd = torch.full((ld,), SENTINEL); hd[:d] = torch.from_numpy(h); hd = hd.to(DEV)
+    X, Y, Go = gen.state(n, d, 1), gen.state(n, d, 2), gen.state(n, d, 3)
+    if bf:
+        X, Y = OO.round_bf16(X), OO.round_bf16(Y)
+    bd = to_dev(b, ld)
+    cols = np.arange(d)
+    Xf, Yf, Gf = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld)
+    Xs, Ys, Gos, Gns = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld), to_dev(np.zeros((n, d)), ld)
+    Xr, Yr, Gor = X.astype(np.float64), Y.astype(np.float64), Go.astype(np.float64)
+    for t in range(2):
+        ctx.step_quadratic(Xf, Yf, Gf, hd, bd, alpha, K, sigma=sigma, seed=seed, step=t, eta=eta)
+        ctx.grad_quadratic_diag(Xs, hd, bd, Gns, sigma=sigma, seed=seed, step=t)
+        ctx.step(Xs, Ys, Gns, Gos, alpha, K, eta)
+        Gos, Gns = Gns, Gos
+        Gn = OO.grad_quadratic_diag(Xr, h, b, ON.normal_noise(seed, t, n, cols), sigma)
+        if t == 0:
+            S = amax(Xr, Yr, Gn, Gor)
+            Xn, Yn = OG.detag_step(Xr, Yr, Gn, Gor, W, alpha, K, eta)
+            assert rel_err(to_host(Gf, d), Gn, S) < TOL_F32
+            assert rel_err(to_host(Xf, d), Xn, S) < tol
+            assert rel_err(to_host(Yf, d), Yn, S) < tol
+        torch.cuda.synchronize()
+        assert torch.equal(Xf, Xs) and torch.equal(Yf, Ys) and torch.equal(Gf, Gos)
+        Xr, Yr, Gor = to_host(Xf, d), to_host(Yf, d), to_host(Gf, d)
+    assert padding_ok(Xf, d) and padding_ok(Yf, d) and padding_ok(Gf, d)
 
 
 # ---------------------------------------------------------------------------
