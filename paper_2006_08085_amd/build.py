@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdetag.so")
 
-SOURCES = ["topology.cpp", "consensus.cpp", "detag_api.hip", "k_stream.hip", "k_fused.hip", "k_fused_quad.hip", "k_fused_generic.hip",
+SOURCES = ["topology.cpp", "consensus.cpp", "detag_api.hip", "k_stream.hip", "k_fused.hip", "k_fused_quad.hip", "k_fused_generic.hip", "k_fused_generic_quad.hip",
            "k_diag.hip", "k_grad.hip", "k_softmax.hip", "k_consensus.hip", "k_dense.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
