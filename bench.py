@@ -269,7 +269,9 @@ def main():
         kernel = "mean_kernel (detag_mean)"
     elif alg == "dpsgd":
         bpe = 2 * sb + 4
-        kernel = (("fused_structured_kernel, D-PSGD mode" if structured and not per_round else "gossip_round_kernel")
+        staged = n <= 256 and n * ld * sb >= (128 << 20)      # the launcher's rule for the LDS-staged round kernel
+        kernel = (("fused_structured_kernel, D-PSGD mode" if structured and not per_round else
+                   "gossip_round_tile_kernel, in place" if staged else "copy + gossip_round_kernel")
                   + " (detag_dpsgd_step)")
     elif fused:
         bpe = 4 * sb + 12

@@ -555,6 +555,10 @@ detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, d
                                            stream);
     return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
   }
+  if (round_stages_tile(ctx->shape)) {  // every column tile is read whole before it is written: in place, 12 B per element
+    const int rc = launch_dpsgd(ctx->shape, dev_csr(ctx), X_dev, X_dev, G_dev, float(alpha), stream);
+    return rc ? hip_fail(ctx, "dpsgd", rc) : DETAG_OK;
+  }
   if (detag_status st = need_scratch(ctx, 0, 1, stream)) return st;
   int rc = launch_copy_state(ctx->shape, X_dev, ctx->scratch[0], stream);
   if (!rc) rc = launch_dpsgd(ctx->shape, dev_csr(ctx), ctx->scratch[0], X_dev, G_dev, float(alpha), stream);

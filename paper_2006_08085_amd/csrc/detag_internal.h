@@ -107,6 +107,7 @@ int launch_track(const Shape &s, void *Y, const float *Gn, const float *Go, void
 int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const float *Go, float alpha,
                         void *stream);
 // X = c_mix * (W^T Xin) - alpha*G  (D-PSGD); Xin != X
+bool round_stages_tile(const Shape &s);
 int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
                  void *stream);
 int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream);

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(64 * kTileWaves) void gossip_round_tile_kernel(int 
                                                                          const int32_t *__restrict__ rowptr,
                                                                          const int32_t *__restrict__ colidx,
                                                                          const float *__restrict__ vals,
-                                                                         const ST *__restrict__ cur, const ST *prev,
+                                                                         const ST *cur, const ST *prev,
                                                                          ST *out, const float *__restrict__ G,
                                                                          float c_mix, float eta, float alpha) {
   extern __shared__ float tile_lds[];  // n x 64
@@ -344,7 +344,7 @@ template <typename ST, bool HAS_G>
 int launch_round_t(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, const float *G,
                    float c_mix, float eta, float alpha, void *stream) {
   auto st = static_cast<hipStream_t>(stream);
-  if (s.n <= kTileRowsMax && int64_t(s.n) * s.ld * int64_t(sizeof(ST)) >= kTileMinBytes) {
+  if (round_stages_tile(s)) {
     const dim3 tgrid(ceil_div_i64(s.d, kTileCols));
     const size_t lds_bytes = size_t(s.n) * kTileCols * sizeof(float);
 #define DETAG_TILE_GO(RW)                                                                                      \
@@ -481,6 +481,12 @@ int launch_widen(const Shape &s, const void *src_bf16, float *dst, void *stream)
 
 int launch_narrow(const Shape &s, const float *src, void *dst_bf16, void *stream) {
   return launch_convert_t<float, bf16_t>(s, src, dst_bf16, stream);
+}
+
+// Whether a round on this shape takes the LDS-staged tile kernel.  That kernel reads all n rows of a column tile
+// before it writes any, so its output may also be written over z_r itself (detag_dpsgd_step then needs no copy).
+bool round_stages_tile(const Shape &s) {
+  return s.n <= kTileRowsMax && int64_t(s.n) * s.ld * int64_t(s.bf16 ? 2 : 4) >= kTileMinBytes;
 }
 
 int launch_gossip_round(const Shape &s, const DevCsr &w, const void *cur, const void *prev, void *out, float eta,
