@@ -70,9 +70,15 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(int n, int6
 
 __global__ __launch_bounds__(kThreads) void sum_partials_kernel(int64_t count, const double *__restrict__ partials,
                                                                 double *__restrict__ out) {
-  double acc = 0.0;
-  for (int64_t k = threadIdx.x; k < count; k += kThreads) acc += partials[k];
-  const double t = block_sum(acc);
+  // four independent sums per thread: one chain of dependent additions per thread leaves the block waiting on one
+  // load at a time (42 us for the 43,648 partial sums of d = 11.2 M); the order of the additions is fixed
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  int64_t k = threadIdx.x;
+  for (; k + 3 * kThreads < count; k += 4 * kThreads) {
+    a0 += partials[k], a1 += partials[k + kThreads], a2 += partials[k + 2 * kThreads], a3 += partials[k + 3 * kThreads];
+  }
+  for (; k < count; k += kThreads) a0 += partials[k];
+  const double t = block_sum((a0 + a1) + (a2 + a3));
   if (threadIdx.x == 0) *out = t;
 }
 
