@@ -650,3 +650,60 @@ def test_step_quadratic_with_per_worker_curvature(kind, n, dtype, variant):
     torch.cuda.synchronize()
     assert torch.equal(Xf, Xs) and torch.equal(Yf, Ys) and torch.equal(Gf, Gns)
     assert padding_ok(Xf, d) and padding_ok(Yf, d) and padding_ok(Gf, d) and padding_ok(hd, d)
+
+
+# ---------------------------------------------------------------------------
+# matrices narrower than one vector, one wavefront or one tile
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kind,n", [("ring", 8), ("torus88", 64), ("rr", 12), ("asym", 5)])
+@pytest.mark.parametrize("path", [D.DETAG_PATH_AUTO, D.DETAG_PATH_PER_ROUND])
+@pytest.mark.parametrize("d,ld", [(1, 1), (3, 3), (3, 64), (63, 63), (65, 128)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_very_narrow_matrices(kind, n, path, d, ld, dtype):
+    """d = 1, 3, 63, 65 columns with the pitch equal to d (odd: no vector access is aligned) and padded: every
+    entry point of the step against the oracle, padding untouched."""
+    bf = dtype == "bf16"
+    tdt, tol = (torch.bfloat16, TOL_BF16) if bf else (torch.float32, TOL_F32)
+    ctx, W = make_ctx(kind, n, d, ld, D.DETAG_BF16 if bf else D.DETAG_F32)
+    ctx.set_path(path)
+    eta, alpha, K, sigma, seed = eta_for(W), 0.3, 3, 0.1, 5
+    rnd = OO.round_bf16 if bf else (lambda a: a)
+    X, Y, Gn, Go = rnd(gen.state(n, d, 1)), rnd(gen.state(n, d, 2)), gen.state(n, d, 3), gen.state(n, d, 4)
+    S = amax(X, Y, Gn, Go)
+    # gossip alone
+    Zd = to_dev(X, ld, tdt)
+    ctx.gossip_accel(Zd, K, eta)
+    assert rel_err(to_host(Zd, d), OG.accelerated_gossip(X, W, K, eta), amax(X)) < tol and padding_ok(Zd, d)
+    # phase, both variants
+    for variant, vcode in (("atc", D.DETAG_VARIANT_ATC), ("alg2", D.DETAG_VARIANT_ALG2)):
+        Xd, Yd, Gnd, God = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Gn, ld), to_dev(Go, ld)
+        ctx.step(Xd, Yd, Gnd, God, alpha, K, eta, vcode)
+        Xr, Yr = OG.detag_step(X, Y, Gn, Go, W, alpha, K, eta, variant)
+        assert rel_err(to_host(Xd, d), Xr, S) < tol and rel_err(to_host(Yd, d), Yr, S) < tol
+        assert padding_ok(Xd, d) and padding_ok(Yd, d)
+    # D-PSGD step, worker mean, consensus distance
+    Xd, Gd = to_dev(X, ld, tdt), to_dev(Gn, ld)
+    ctx.dpsgd_step(Xd, Gd, alpha)
+    assert rel_err(to_host(Xd, d), OG.dpsgd_step(X, Gn, W, alpha), S) < tol and padding_ok(Xd, d)
+    Xd = to_dev(X, ld, tdt)
+    assert np.abs(ctx.mean(Xd).cpu().numpy()[:d] - X.astype(np.float64).mean(axis=0)).max() < 1e-6 * amax(X)
+    ce = float(ctx.consensus_error(Xd).item())
+    ref = float(((X.astype(np.float64) - X.astype(np.float64).mean(axis=0)) ** 2).sum())
+    assert abs(ce - ref) <= 1e-10 * max(ref, 1.0)
+    # gradient query, alone and fused with the phase where the context has an on-chip kernel
+    h, b = gen.quadratic_problem(n, d, seed=3)
+    hd = torch.full((max(ld, 4),), SENTINEL); hd[:d] = torch.from_numpy(h); hd = hd.to(DEV)
+    bd, cols = to_dev(b, ld), np.arange(d)
+    Gref = OO.grad_quadratic_diag(X.astype(np.float64), h, b, ON.normal_noise(seed, 1, n, cols), sigma)
+    Xd, Gd = to_dev(X, ld, tdt), to_dev(np.zeros((n, d)), ld)
+    ctx.grad_quadratic_diag(Xd, hd, bd, Gd, sigma=sigma, seed=seed, step=1)
+    S2 = amax(X, Gref, Go)
+    assert rel_err(to_host(Gd, d), Gref, S2) < TOL_F32 and padding_ok(Gd, d)
+    if path == D.DETAG_PATH_AUTO and ctx.has_fused():
+        Xd, Yd, Gd = to_dev(X, ld, tdt), to_dev(Y, ld, tdt), to_dev(Go, ld)
+        ctx.step_quadratic(Xd, Yd, Gd, hd, bd, alpha, K, sigma=sigma, seed=seed, step=1, eta=eta)
+        Xr, Yr = OG.detag_step(X, Y, Gref, Go, W, alpha, K, eta)
+        S3 = amax(X, Y, Gref, Go)
+        assert rel_err(to_host(Gd, d), Gref, S3) < TOL_F32
+        assert rel_err(to_host(Xd, d), Xr, S3) < tol and rel_err(to_host(Yd, d), Yr, S3) < tol
+        assert padding_ok(Xd, d) and padding_ok(Yd, d) and padding_ok(Gd, d)
