@@ -200,3 +200,59 @@ def test_config5_full_size_sampled_columns(path):
     assert rel_err(take(Y), Yr, S, floor=TIGHT) < TOL_BF16
     # fp32 on chip, rounded once: within half a bf16 ulp of the oracle wherever the value is not tiny
     assert rel_err(take(X), Xr) < 2.0 ** -8 and rel_err(take(Y), Yr) < 2.0 ** -8
+
+
+@pytest.mark.parametrize("family", ["register", "lds", "per_round"])
+def test_matrices_beyond_4_gib(family):
+    """State matrices of more than 2^32 bytes each (byte offsets of the last rows do not fit 32 bits): one step of
+    each kernel family on sampled columns against the oracle, the last ragged tile included, and the diagnostics
+    against torch on the whole matrix."""
+    dev = torch.device(DEV)
+    if family == "lds":
+        n, d = 128, 8_500_003
+        topo = D.Topology.random_regular(4, 3)
+    else:
+        n, d = 64, 17_000_003
+        topo = D.Topology.torus(8, 8)
+    ld = D.padded_ld(d)
+    assert n * ld * 4 > 2 ** 32
+    ctx = D.detag_create(topo, n, d, ld)
+    W = ctx.dense_W()
+    OT.check_gossip_matrix(W)
+    eta = OT.eta_from_lambda(OT.spectrum(W)[2])
+    K, alpha, sigma, seed, step = 3, 0.5, 0.1, 9, 4
+    b = gen.device_normal(n, d, ld, seed, 1, dev)
+    h = gen.device_log_uniform(d, ld, seed, 2, dev, 1e-3, 1.0)
+    X = gen.device_normal(n, d, ld, seed, 3, dev)
+    Y = gen.device_normal(n, d, ld, seed, 4, dev)
+    G = gen.device_normal(n, d, ld, seed, 5, dev)
+    cols = _sample_columns(d, np.random.default_rng(2))
+    cols = cols[cols < d]
+    idx = torch.from_numpy(cols).to(dev)
+    take = lambda t: t[:, idx].double().cpu().numpy()
+    Xs, Ys, Gos, bs = take(X), take(Y), take(G), take(b)
+    hs = h[idx].double().cpu().numpy()
+    pad = [t[:, d:].clone() for t in (X, Y, G)]
+    # diagnostics on the untouched state: every column enters
+    mean_ref = X[:, :d].double().mean(dim=0)
+    assert (ctx.mean(X)[:d].double() - mean_ref).abs().max().item() < 1e-6
+    ce_ref = ((X[:, :d].double() - mean_ref) ** 2).sum().item()
+    assert abs(float(ctx.consensus_error(X).item()) - ce_ref) <= 1e-9 * ce_ref
+    del mean_ref
+    Gns = OO.grad_quadratic_diag(Xs, hs, bs, ON.normal_noise(seed, step, n, cols), sigma)
+    Xr, Yr = OG.detag_step(Xs, Ys, Gns, Gos, W, alpha, K, eta)
+    S = amax(Xs, Ys, Gns, Gos)
+    if family == "per_round":
+        ctx.set_path(D.DETAG_PATH_PER_ROUND)
+        Gn = D.new_matrix(n, d, ld, device=dev)
+        ctx.grad_quadratic_diag(X, h, b, Gn, sigma=sigma, seed=seed, step=step)
+        ctx.step(X, Y, Gn, G, alpha, K)
+        G = Gn
+    else:
+        assert ctx.kernel() == (D.DETAG_KERNEL_LDS_TILE if family == "lds" else D.DETAG_KERNEL_REGISTER_TILE)
+        ctx.step_quadratic(X, Y, G, h, b, alpha, K, sigma=sigma, seed=seed, step=step)
+    assert rel_err(take(G), Gns, S, floor=TIGHT) < TOL_F32
+    assert rel_err(take(X), Xr, S, floor=TIGHT) < TOL_F32
+    assert rel_err(take(Y), Yr, S, floor=TIGHT) < TOL_F32
+    for t, p in zip((X, Y) if family == "per_round" else (X, Y, G), pad):
+        assert torch.equal(t[:, d:], p)
