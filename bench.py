@@ -254,11 +254,15 @@ def main():
     E = n * d
     rounds_bytes = 4 * (3 * K - 1)      # per matrix, one launch per round: first round reads 1 and writes 1, the rest read 2, write 1
     note = None
+    # the launcher's rule for one round per launch: the fp32 working matrix decides (bf16 state is widened first)
+    big = n <= 256 and n * ld * 4 >= (128 << 20)
+    round_kernel = "structured_round_kernel" if structured and big else "gossip_round_tile_kernel" if big \
+        else "gossip_round_kernel"
     # algorithmic bytes per element of what the two events bracket: state read and written once each by the
     # K-round kernels; one launch per round moves every round through HBM (fp32 scratch whatever the state type)
     if what == "gossip":
         bpe = rounds_bytes if per_round else 2 * sb
-        kernel = ("gossip_round_tile_kernel x%d" % K) if per_round and n <= 256 else ("gossip_round_kernel x%d" % K) if per_round else \
+        kernel = ("%s x%d" % (round_kernel, K)) if per_round else \
             ("fused_structured_kernel, gossip mode" if structured else "fused_generic_kernel, gossip mode")
         kernel += " (detag_gossip_accel)"
     elif what == "stream":
@@ -282,7 +286,7 @@ def main():
     elif per_round:
         bpe = 24 + 2 * rounds_bytes
         kernel = "elementwise_kernel + %s x%d (detag_step, one launch per round)" % (
-            "gossip_round_tile_kernel" if n <= 256 else "gossip_round_kernel", 2 * K)
+            round_kernel, 2 * K)
         note = "sum over the launches of one detag_step call; every round crosses HBM"
     else:
         bpe = 4 * sb + 8

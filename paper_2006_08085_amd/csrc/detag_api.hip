@@ -186,6 +186,16 @@ detag_status dense_poly(detag_ctx *ctx, int K, float eta, const uint16_t **frag,
   return DETAG_OK;
 }
 
+// One round with z_{r-1} given.  Ring and torus contexts with a register-resident kernel take that family's
+// one-round kernel for large matrices (every row read once, 12 B per element at the tile-walk rate); everything
+// else the CSR kernels (LDS-staged from 128 MiB on, cache-served below).
+int round_launch(const detag_ctx *ctx, const Shape &s, const void *cur, const void *prev, void *out, float eta,
+                 void *stream) {
+  if (fused_structured_available(ctx->W) && round_stages_tile(s))
+    return launch_structured_round(s, ctx->W, cur, prev, out, eta, stream);
+  return launch_gossip_round(s, dev_csr(ctx), cur, prev, out, eta, stream);
+}
+
 // Algorithm 3 with one launch per round on an fp32 matrix A.  z_r lives in A or
 // in scratch; a round may write over its own z_{r-1} (each output element reads
 // only its own previous value) but never over z_r, which every neighbour reads.
@@ -195,8 +205,7 @@ detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, voi
   if (detag_status st = need_scratch(ctx, 0, nscratch, stream)) return st;
   void *B = ctx->scratch[0], *C = ctx->scratch[1];
   const Shape s = as_f32(ctx->shape);
-  const DevCsr w = dev_csr(ctx);
-  int rc = launch_gossip_round(s, w, A, A, B, eta, stream);  // z1 -> B
+  int rc = round_launch(ctx, s, A, A, B, eta, stream);  // z1 -> B
   if (rc) return hip_fail(ctx, "gossip round", rc);
   if (K == 1) {
     rc = launch_copy_state(s, B, A, stream);
@@ -205,13 +214,13 @@ detag_status gossip_per_round_f32(detag_ctx *ctx, void *A, int K, float eta, voi
   int r = 1;           // next round computes z_{r+1}
   void *cur = B, *prev = A;
   if (K % 2 == 1) {    // shift parity once through the third buffer: z2 -> C, z3 -> A
-    rc = launch_gossip_round(s, w, B, A, C, eta, stream);
-    if (!rc) rc = launch_gossip_round(s, w, C, B, A, eta, stream);
+    rc = round_launch(ctx, s, B, A, C, eta, stream);
+    if (!rc) rc = round_launch(ctx, s, C, B, A, eta, stream);
     if (rc) return hip_fail(ctx, "gossip round", rc);
     r = 3, cur = A, prev = C;
   }
   for (; r < K; ++r) {  // z_{r+1} overwrites z_{r-1}
-    rc = launch_gossip_round(s, w, cur, prev, prev, eta, stream);
+    rc = round_launch(ctx, s, cur, prev, prev, eta, stream);
     if (rc) return hip_fail(ctx, "gossip round", rc);
     void *t = cur; cur = prev; prev = t;
   }
@@ -574,7 +583,7 @@ detag_status detag_gossip_round(detag_ctx *ctx, const void *Zcur_dev, const void
   if (Zout_dev == Zcur_dev) return set_err(ctx, DETAG_EINVAL, "Zout must not be Zcur: every neighbour reads Zcur");
   float e;
   if (detag_status st = resolve_eta(ctx, eta, &e)) return st;
-  const int rc = launch_gossip_round(ctx->shape, dev_csr(ctx), Zcur_dev, Zprev_dev, Zout_dev, e, stream);
+  const int rc = round_launch(ctx, ctx->shape, Zcur_dev, Zprev_dev, Zout_dev, e, stream);
   return rc ? hip_fail(ctx, "gossip round", rc) : DETAG_OK;
 }
 

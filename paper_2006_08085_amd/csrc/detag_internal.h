@@ -108,6 +108,8 @@ int launch_update_track(const Shape &s, void *X, void *Y, const float *Gn, const
                         void *stream);
 // X = c_mix * (W^T Xin) - alpha*G  (D-PSGD); Xin != X
 bool round_stages_tile(const Shape &s);
+int launch_structured_round(const Shape &s, const HostW &W, const void *cur, const void *prev, void *out, float eta,
+                            void *stream);
 int launch_dpsgd(const Shape &s, const DevCsr &w, const void *Xin, void *X, const float *G, float alpha,
                  void *stream);
 int launch_copy_state(const Shape &s, const void *src, void *dst, void *stream);

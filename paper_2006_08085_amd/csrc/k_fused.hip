@@ -132,6 +132,35 @@ __global__ __launch_bounds__(kThreads, waves_per_simd(T::n, MODE)) void fused_st
   }
 }
 
+// One round of Algorithm 3 with z_{r-1} given (one iteration of Algorithm 2's communication), for the patterns above:
+//   out = z_r + b * sum_nb (z_j - z_i) + eta * (z_r - z_{r-1}),   b = (1+eta) * w_nb.
+// All n rows of z_r in registers, z_{r-1} streamed a few rows ahead of the stores: 12 B per element (fp32), every row
+// read once.  Every row of z_r is in registers before the first store and a row of z_{r-1} is read before the same
+// row of out is written, so out may be z_{r-1} (the caller's usual choice) or z_r itself.
+template <class T, typename ST>
+__global__ __launch_bounds__(kThreads, waves_per_simd(T::n, 0)) void structured_round_kernel(
+    const ST *cur, const ST *prev, ST *out, int64_t d, int64_t ld, Coef c) {
+  constexpr int N = T::n;
+  constexpr int D = kRowsAhead < N ? kRowsAhead : N;
+  const int64_t tile = xcd_tile(blockIdx.x, gridDim.x) * kThreads;
+  const uint32_t valid = uint32_t(d - tile < kThreads ? d - tile : kThreads);
+  const uint32_t so = threadIdx.x * uint32_t(sizeof(ST));
+  float u[N], lp[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) u[i] = buf_load<ST>(row_of(cur, tile, ld, i, valid), so);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < D; ++i) lp[i] = buf_load<ST>(row_of(prev, tile, ld, i, valid), so);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + D < N) lp[i + D] = buf_load<ST>(row_of(prev, tile, ld, i + D, valid), so);
+    const float v = fmaf(c.eta, u[i] - lp[i], c.b * lap<T>(u, i));
+    buf_store<ST>(row_of(out, tile, ld, i, valid), so, u[i] + v);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <class T, typename ST>
 int launch_t(const Shape &s, int mode, void *X, void *Y, const float *Gn, const float *Go, const Coef &c,
              float alpha, int K, void *stream) {
@@ -168,6 +197,44 @@ int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, v
   if (K < 1 || !fused_structured_available(W)) return -1;
   const Coef c = make_coef(W, eta);
 #define DETAG_GO(T) return launch_s<T>(s, mode, X, Y, Gn, Go, c, alpha, K, stream)
+  if (W.structure == kRing) {
+    switch (W.n) {
+      case 4: DETAG_GO(Ring<4>);
+      case 8: DETAG_GO(Ring<8>);
+      case 16: DETAG_GO(Ring<16>);
+      case 32: DETAG_GO(Ring<32>);
+      case 64: DETAG_GO(Ring<64>);
+    }
+  } else if (W.structure == kTorus) {
+    using T88 = Torus<8, 8>;
+    using T44 = Torus<4, 4>;
+    using T48 = Torus<4, 8>;
+    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
+    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
+    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
+  }
+#undef DETAG_GO
+  return -1;
+}
+
+int launch_structured_round(const Shape &s, const HostW &W, const void *cur, const void *prev, void *out, float eta,
+                            void *stream) {
+  if (!fused_structured_available(W)) return -1;
+  const Coef c = make_coef(W, eta);
+  const dim3 grid(ceil_div_i64(s.d, kThreads));
+  auto st = static_cast<hipStream_t>(stream);
+#define DETAG_GO(T)                                                                                                  \
+  do {                                                                                                               \
+    if (s.bf16)                                                                                                      \
+      structured_round_kernel<T, bf16_t><<<grid, kThreads, 0, st>>>(static_cast<const bf16_t *>(cur),                \
+                                                                    static_cast<const bf16_t *>(prev),               \
+                                                                    static_cast<bf16_t *>(out), s.d, s.ld, c);       \
+    else                                                                                                             \
+      structured_round_kernel<T, float><<<grid, kThreads, 0, st>>>(static_cast<const float *>(cur),                  \
+                                                                   static_cast<const float *>(prev),                 \
+                                                                   static_cast<float *>(out), s.d, s.ld, c);         \
+    return hip_rc(hipGetLastError());                                                                                \
+  } while (0)
   if (W.structure == kRing) {
     switch (W.n) {
       case 4: DETAG_GO(Ring<4>);
