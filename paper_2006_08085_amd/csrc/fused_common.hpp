@@ -38,6 +38,26 @@ struct Torus {
   }
 };
 
+// The patterns the register-resident kernels are compiled for.  Calls f with a value of the pattern type that
+// matches W (Ring<N> or Torus<R, C>) and returns its result; -1 if W is none of them.
+template <class F>
+int with_pattern(const HostW &W, F &&f) {
+  if (W.structure == kRing) {
+    switch (W.n) {
+      case 4: return f(Ring<4>{});
+      case 8: return f(Ring<8>{});
+      case 16: return f(Ring<16>{});
+      case 32: return f(Ring<32>{});
+      case 64: return f(Ring<64>{});
+    }
+  } else if (W.structure == kTorus) {
+    if (W.trows == 8 && W.tcols == 8) return f(Torus<8, 8>{});
+    if (W.trows == 4 && W.tcols == 4) return f(Torus<4, 4>{});
+    if (W.trows == 4 && W.tcols == 8) return f(Torus<4, 8>{});
+  }
+  return -1;
+}
+
 // One round of Algorithm 3 in velocity form.  With v_r = z_r - z_{r-1} (v_0 = 0, since z_{-1} = z_0),
 //   z_{r+1} = (1+eta) W^T z_r - eta z_{r-1}
 // is the same as

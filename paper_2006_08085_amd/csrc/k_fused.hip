@@ -186,73 +186,31 @@ int launch_s(const Shape &s, int mode, void *X, void *Y, const float *Gn, const 
 }  // namespace
 
 bool fused_structured_available(const HostW &W) {
-  if (W.structure == kRing) return W.n == 4 || W.n == 8 || W.n == 16 || W.n == 32 || W.n == 64;
-  if (W.structure == kTorus)
-    return (W.trows == 8 && W.tcols == 8) || (W.trows == 4 && W.tcols == 4) || (W.trows == 4 && W.tcols == 8);
-  return false;
+  return with_pattern(W, [](auto) { return 0; }) == 0;
 }
 
 int launch_fused_structured(const Shape &s, const HostW &W, int mode, void *X, void *Y, const float *Gn,
                             const float *Go, float alpha, int K, float eta, void *stream) {
-  if (K < 1 || !fused_structured_available(W)) return -1;
+  if (K < 1) return -1;
   const Coef c = make_coef(W, eta);
-#define DETAG_GO(T) return launch_s<T>(s, mode, X, Y, Gn, Go, c, alpha, K, stream)
-  if (W.structure == kRing) {
-    switch (W.n) {
-      case 4: DETAG_GO(Ring<4>);
-      case 8: DETAG_GO(Ring<8>);
-      case 16: DETAG_GO(Ring<16>);
-      case 32: DETAG_GO(Ring<32>);
-      case 64: DETAG_GO(Ring<64>);
-    }
-  } else if (W.structure == kTorus) {
-    using T88 = Torus<8, 8>;
-    using T44 = Torus<4, 4>;
-    using T48 = Torus<4, 8>;
-    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
-    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
-    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
-  }
-#undef DETAG_GO
-  return -1;
+  return with_pattern(W, [&](auto t) { return launch_s<decltype(t)>(s, mode, X, Y, Gn, Go, c, alpha, K, stream); });
 }
 
 int launch_structured_round(const Shape &s, const HostW &W, const void *cur, const void *prev, void *out, float eta,
                             void *stream) {
-  if (!fused_structured_available(W)) return -1;
   const Coef c = make_coef(W, eta);
   const dim3 grid(ceil_div_i64(s.d, kThreads));
   auto st = static_cast<hipStream_t>(stream);
-#define DETAG_GO(T)                                                                                                  \
-  do {                                                                                                               \
-    if (s.bf16)                                                                                                      \
-      structured_round_kernel<T, bf16_t><<<grid, kThreads, 0, st>>>(static_cast<const bf16_t *>(cur),                \
-                                                                    static_cast<const bf16_t *>(prev),               \
-                                                                    static_cast<bf16_t *>(out), s.d, s.ld, c);       \
-    else                                                                                                             \
-      structured_round_kernel<T, float><<<grid, kThreads, 0, st>>>(static_cast<const float *>(cur),                  \
-                                                                   static_cast<const float *>(prev),                 \
-                                                                   static_cast<float *>(out), s.d, s.ld, c);         \
-    return hip_rc(hipGetLastError());                                                                                \
-  } while (0)
-  if (W.structure == kRing) {
-    switch (W.n) {
-      case 4: DETAG_GO(Ring<4>);
-      case 8: DETAG_GO(Ring<8>);
-      case 16: DETAG_GO(Ring<16>);
-      case 32: DETAG_GO(Ring<32>);
-      case 64: DETAG_GO(Ring<64>);
-    }
-  } else if (W.structure == kTorus) {
-    using T88 = Torus<8, 8>;
-    using T44 = Torus<4, 4>;
-    using T48 = Torus<4, 8>;
-    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
-    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
-    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
-  }
-#undef DETAG_GO
-  return -1;
+  return with_pattern(W, [&](auto t) {
+    using T = decltype(t);
+    if (s.bf16)
+      structured_round_kernel<T, bf16_t><<<grid, kThreads, 0, st>>>(
+          static_cast<const bf16_t *>(cur), static_cast<const bf16_t *>(prev), static_cast<bf16_t *>(out), s.d, s.ld, c);
+    else
+      structured_round_kernel<T, float><<<grid, kThreads, 0, st>>>(
+          static_cast<const float *>(cur), static_cast<const float *>(prev), static_cast<float *>(out), s.d, s.ld, c);
+    return hip_rc(hipGetLastError());
+  });
 }
 
 }  // namespace detag

@@ -218,27 +218,11 @@ int launch_s(const Shape &s, bool alg2, void *X, void *Y, float *G, const float 
 int launch_fused_quadratic(const Shape &s, const HostW &W, bool alg2, void *X, void *Y, float *G, const float *h,
                            bool h_per_worker, const float *b, float alpha, int K, float eta, float sigma, uint64_t seed,
                            uint32_t step, void *stream) {
-  if (K < 1 || !fused_structured_available(W)) return -1;
+  if (K < 1) return -1;
   const Coef c = make_coef(W, eta);
-#define DETAG_GO(T) return launch_s<T>(s, alg2, X, Y, G, h, h_per_worker, b, c, alpha, K, sigma, seed, step, stream)
-  if (W.structure == kRing) {
-    switch (W.n) {
-      case 4: DETAG_GO(Ring<4>);
-      case 8: DETAG_GO(Ring<8>);
-      case 16: DETAG_GO(Ring<16>);
-      case 32: DETAG_GO(Ring<32>);
-      case 64: DETAG_GO(Ring<64>);
-    }
-  } else if (W.structure == kTorus) {
-    using T88 = Torus<8, 8>;
-    using T44 = Torus<4, 4>;
-    using T48 = Torus<4, 8>;
-    if (W.trows == 8 && W.tcols == 8) DETAG_GO(T88);
-    if (W.trows == 4 && W.tcols == 4) DETAG_GO(T44);
-    if (W.trows == 4 && W.tcols == 8) DETAG_GO(T48);
-  }
-#undef DETAG_GO
-  return -1;
+  return with_pattern(W, [&](auto t) {
+    return launch_s<decltype(t)>(s, alg2, X, Y, G, h, h_per_worker, b, c, alpha, K, sigma, seed, step, stream);
+  });
 }
 
 }  // namespace detag
