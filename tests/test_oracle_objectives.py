@@ -115,6 +115,11 @@ def test_normal_noise_layout_and_box_muller():
     assert z[1, 12] ** 2 + z[1, 13] ** 2 == pytest.approx(-2 * np.log(u0), rel=1e-12)
     u3 = ((int(r[3]) >> 9) + 0.5) / 2 ** 23
     assert np.arctan2(z[1, 15], z[1, 14]) % (2 * np.pi) == pytest.approx(2 * np.pi * u3, rel=1e-9)
+    # the same for the first pair of the block: radius from word 2, angle (cosine first) from word 1
+    u1 = ((int(r[1]) >> 9) + 0.5) / 2 ** 23
+    assert np.arctan2(z[1, 13], z[1, 12]) % (2 * np.pi) == pytest.approx(2 * np.pi * u1, rel=1e-9)
+    u2 = ((int(r[2]) >> 9) + 0.5) / 2 ** 23
+    assert z[1, 14] ** 2 + z[1, 15] ** 2 == pytest.approx(-2 * np.log(u2), rel=1e-12)
     # different step / worker / seed -> different streams
     assert not np.array_equal(z, N.normal_noise(5, 3, n, np.arange(d)))
     assert not np.array_equal(z[0], z[1])

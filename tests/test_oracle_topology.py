@@ -157,6 +157,9 @@ def test_check_rejects_bad_matrices():
     T.check_gossip_matrix(off)                       # still doubly stochastic
     with pytest.raises(ValueError):
         T.check_gossip_matrix(off, gen.edges_ring(6))   # but not on the graph
+    neg = np.array([[1.5, -0.5], [-0.5, 1.5]])       # rows and columns sum to one, entries are not in [0, 1]
+    with pytest.raises(ValueError):
+        T.check_gossip_matrix(neg)
 
 
 def test_neighbour_lists_read_columns():
