@@ -256,7 +256,7 @@ def main():
     note = None
     # the launcher's rule for one round per launch: the fp32 working matrix decides (bf16 state is widened first)
     big = n <= 256 and n * ld * 4 >= (128 << 20)
-    round_kernel = "structured_round_kernel" if structured and big else "gossip_round_tile_kernel" if big \
+    round_kernel = "structured_round_kernel" if structured else "gossip_round_tile_kernel" if big \
         else "gossip_round_kernel"
     # algorithmic bytes per element of what the two events bracket: state read and written once each by the
     # K-round kernels; one launch per round moves every round through HBM (fp32 scratch whatever the state type)

@@ -278,9 +278,10 @@ detag_status detag_dpsgd_step(detag_ctx *ctx, void *X_dev, const float *G_dev, d
  * value); it must not be Zcur.  All three: n x ld, state type.  The caller
  * rotates the buffers.  eta as in detag_gossip_accel.  With bf16 state every
  * call rounds its output (the fused entry points round once per phase).
- * Every row is read once (12 B per element with fp32 state) on matrices of
- * 128 MiB and more with n <= 256; smaller ones and n > 256 read a row once per
- * neighbour, mostly from the caches.
+ * Every row is read once (12 B per element with fp32 state) on ring and torus
+ * contexts of the register-resident family and, for any other W with
+ * n <= 256, on matrices of 128 MiB and more; smaller ones and n > 256 read a
+ * row once per neighbour, mostly from the caches.
  */
 detag_status detag_gossip_round(detag_ctx *ctx, const void *Zcur_dev, const void *Zprev_dev, void *Zout_dev,
                                 double eta, void *stream);
