@@ -167,8 +167,8 @@ detag_status detag_set_path(detag_ctx *ctx, int32_t path /* detag_path */);
  * context with its current path: it depends on the topology and on n, and the
  * families differ in cost by integer factors, so a caller sizing a run should
  * look.  Measured on MI355X, fp32 state unless noted:
- *   DETAG_KERNEL_REGISTER_TILE  ring with n in {4, 8, 16, 32, 64}, torus 4x4,
- *     4x8, 8x8 (built from DETAG_TOPO_RING / DETAG_TOPO_TORUS2D with uniform
+ *   DETAG_KERNEL_REGISTER_TILE  ring with n in {4, 8, 12, 16, 24, 32, 48,
+ *     64}, torus 4x4, 4x8, 8x8 (built from DETAG_TOPO_RING / DETAG_TOPO_TORUS2D with uniform
  *     weights and any kappa).  All n rows of a column in registers, K rounds
  *     on chip: 24 B per element and phase whatever K is, 0.66 of HBM peak at
  *     n = 64, d = 11.2 M.  Only this family serves detag_step_quadratic with

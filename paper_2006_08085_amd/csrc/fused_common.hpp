@@ -46,8 +46,11 @@ int with_pattern(const HostW &W, F &&f) {
     switch (W.n) {
       case 4: return f(Ring<4>{});
       case 8: return f(Ring<8>{});
+      case 12: return f(Ring<12>{});
       case 16: return f(Ring<16>{});
+      case 24: return f(Ring<24>{});
       case 32: return f(Ring<32>{});
+      case 48: return f(Ring<48>{});
       case 64: return f(Ring<64>{});
     }
   } else if (W.structure == kTorus) {

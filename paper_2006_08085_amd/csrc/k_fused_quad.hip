@@ -35,8 +35,15 @@ using namespace fused;
 constexpr int kParkedRows = 48;
 // HPW: the curvature h is an n x ld matrix (one row per worker, one more streamed array: 32 B per element) instead
 // of one d-vector shared by all workers.
+// Wavefronts per SIMD asked of the register allocator: three with the parked rows at 64 workers, else the phase
+// kernels' figure, one less where all rows' loads of five arrays are in flight at once beside the three resident
+// arrays (12 workers with per-worker curvature: 16 bytes of scratch per lane otherwise).
+constexpr int quad_waves(int n, bool hpw) {
+  return n >= 64 ? 3 : waves_per_simd(n, 1) - (hpw && n == 12 ? 1 : 0);
+}
+
 template <class T, typename ST, bool HPW>
-__global__ __launch_bounds__(kThreads, (T::n >= 64 ? 3 : waves_per_simd(T::n, 1))) void fused_quadratic_kernel(
+__global__ __launch_bounds__(kThreads, quad_waves(T::n, HPW)) void fused_quadratic_kernel(
     ST *X, ST *Y, float *G, const float *__restrict__ h, const float *__restrict__ b, int64_t d, int64_t ld, Coef c,
     float alpha, int K, float sigma, uint32_t seed_lo, uint32_t seed_hi, uint32_t step) {
   constexpr int N = T::n;

@@ -352,7 +352,8 @@ def test_which_kernel_a_topology_gets():
     """The kernel family is a function of (topology, n, path); the families differ in cost by integer factors
     (see detag_get_kernel in detag.h), so the table is pinned."""
     REG, LDS, PER, DENSE = D.DETAG_KERNEL_REGISTER_TILE, D.DETAG_KERNEL_LDS_TILE, D.DETAG_KERNEL_PER_ROUND, D.DETAG_KERNEL_DENSE
-    ring = {1: LDS, 2: LDS, 3: LDS, 4: REG, 5: LDS, 7: LDS, 8: REG, 12: LDS, 16: REG, 24: LDS, 32: REG, 33: LDS, 64: REG,
+    ring = {1: LDS, 2: LDS, 3: LDS, 4: REG, 5: LDS, 7: LDS, 8: REG, 12: REG, 16: REG, 20: LDS, 24: REG, 32: REG, 33: LDS,
+            48: REG, 64: REG,
             65: LDS, 128: LDS, 256: LDS, 257: PER}
     for n, want in ring.items():
         assert D.detag_create(D.Topology.ring(), n, 16).kernel() == want, ("ring", n)

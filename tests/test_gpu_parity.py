@@ -56,7 +56,8 @@ def test_gossip_per_round_unaligned_pitch_uses_scalar_path():
     assert padding_ok(Zd, d)
 
 
-@pytest.mark.parametrize("kind,n", [("ring", 4), ("ring", 8), ("ring", 16), ("ring", 32), ("ring", 64),
+@pytest.mark.parametrize("kind,n", [("ring", 4), ("ring", 8), ("ring", 12), ("ring", 16), ("ring", 24), ("ring", 32),
+                                    ("ring", 48), ("ring", 64),
                                     ("torus44", 16), ("torus48", 32), ("torus88", 64), ("ring_slack", 16)])
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 7, 8])
 def test_gossip_fused_matches_oracle(kind, n, K):
@@ -104,7 +105,9 @@ def test_track_matches_oracle():
     assert padding_ok(Yd, d)
 
 
-STEP_CASES = [("ring", 8, D.DETAG_PATH_FUSED), ("ring", 8, D.DETAG_PATH_PER_ROUND),
+STEP_CASES = [("ring", 12, D.DETAG_PATH_FUSED), ("ring", 24, D.DETAG_PATH_FUSED), ("ring", 48, D.DETAG_PATH_FUSED),
+              ("ring", 24, D.DETAG_PATH_PER_ROUND),
+              ("ring", 8, D.DETAG_PATH_FUSED), ("ring", 8, D.DETAG_PATH_PER_ROUND),
               ("ring", 16, D.DETAG_PATH_FUSED), ("ring", 32, D.DETAG_PATH_FUSED),
               ("torus88", 64, D.DETAG_PATH_FUSED), ("torus88", 64, D.DETAG_PATH_PER_ROUND),
               ("torus48", 32, D.DETAG_PATH_FUSED), ("asym", 5, D.DETAG_PATH_PER_ROUND),
@@ -442,7 +445,8 @@ def test_config5_shape_bf16_short_run():
 # ---------------------------------------------------------------------------
 # gradient query + phase in one kernel
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 16), ("torus48", 32), ("torus88", 64), ("ring", 64)])
+@pytest.mark.parametrize("kind,n", [("ring", 8), ("ring", 12), ("ring", 16), ("ring", 24), ("ring", 48), ("torus48", 32),
+                                    ("torus88", 64), ("ring", 64)])
 @pytest.mark.parametrize("sigma", [0.0, 0.1])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("variant", ["atc", "alg2"])
@@ -619,7 +623,7 @@ def test_one_round_with_lds_staged_tile(n, graph, dtype, pad):
     assert rel_err(to_host(zd, d), OG.accelerated_gossip(cur, W, K, eta), amax(cur)) < tol and padding_ok(zd, d)
 
 
-@pytest.mark.parametrize("kind,n", [("ring", 16), ("torus88", 64)])
+@pytest.mark.parametrize("kind,n", [("ring", 12), ("ring", 16), ("ring", 48), ("torus88", 64)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("variant", ["atc", "alg2"])
 def test_step_quadratic_with_per_worker_curvature(kind, n, dtype, variant):
