@@ -447,3 +447,12 @@ def test_random_graphs_build_and_agree_with_the_oracle(seed):
         assert np.allclose(f.dense(r), ref[r], rtol=0, atol=1e-15)
         prod = f.dense(r) @ prod
     assert np.allclose(prod, np.full((n, n), 1.0 / n), atol=1e-12)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The library has no cross-GPU code: the benchmark says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
